@@ -1,0 +1,194 @@
+/*
+ * radixmlp.h - C ABI of the MI355X (gfx950) deduplicated-prefill library.
+ *
+ * The library implements the hot path of RadixMLP: a causal (Qwen3-style) decoder prefill
+ * in which every position-wise operation runs on the unique prefix-trie rows ("compact
+ * space", N' rows) and only causal attention runs on the full ragged layout (N rows)
+ * (paper: Approach, "The RadixMLP Layout" and "Integration with Attention"; Algorithm 1).
+ *
+ * Conventions
+ *   - Every array pointer is a DEVICE pointer unless its name ends in _host.
+ *   - `stream` is a hipStream_t passed as void*; all device work is enqueued on it and,
+ *     unless stated otherwise, the call returns without waiting for it.
+ *   - The library never allocates caller-visible memory.  Scratch memory is a workspace
+ *     the caller allocates (size from the *_workspace_bytes calls, 256-byte aligned) and
+ *     passes to every call; calls that share a workspace must be ordered on one stream.
+ *   - Every function returns 0 (RADIX_OK) or a negative radix_status.  Argument errors that
+ *     are visible on the host are reported before anything is launched and nothing is
+ *     written.  Errors in device-resident data (cu_seqlens not monotone, token id out of
+ *     range) are recorded by the kernels in a status word inside the workspace; the
+ *     kernels then leave outputs untouched or clamp the offending index, never read or
+ *     write out of bounds, and the error is returned by radix_build_index itself when
+ *     n_compact_host != NULL, else by radix_device_status.
+ *   - Indices are 32-bit: N < 2^31.  Token ids and position ids must be >= 0.
+ */
+#ifndef RADIXMLP_H
+#define RADIXMLP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum radix_status {
+    RADIX_OK = 0,
+    RADIX_ERR_NULL_POINTER = -1,
+    RADIX_ERR_BAD_SIZE = -2,          /* negative B or N, N >= 2^31, n_compact > N, ... */
+    RADIX_ERR_UNSUPPORTED = -3,       /* head_dim / dtype / shape the kernels do not cover */
+    RADIX_ERR_WORKSPACE_TOO_SMALL = -4,
+    RADIX_ERR_MISALIGNED = -5,        /* pointer not aligned as documented */
+    RADIX_ERR_BAD_CU_SEQLENS = -6,    /* device data: cu_seqlens[0] != 0, decreasing, or last != N */
+    RADIX_ERR_BAD_TOKEN = -7,         /* device data: token id < 0 or >= vocab, or position id out of range */
+    RADIX_ERR_HIP = -8,               /* a HIP runtime call failed */
+    RADIX_ERR_BAD_CONFIG = -9         /* inconsistent model configuration */
+} radix_status;
+
+typedef enum radix_dtype { RADIX_F32 = 0, RADIX_BF16 = 1 } radix_dtype;
+
+/* Shape of the decoder (paper: Background, Eqs. 1-2 and Eq. 5). */
+typedef struct radix_model_config {
+    int32_t n_layers;
+    int32_t d;           /* hidden size */
+    int32_t n_q_heads;   /* Hq */
+    int32_t n_kv_heads;  /* Hkv, divides Hq */
+    int32_t head_dim;    /* hd: even, <= 128; the bf16 path requires 128 */
+    int32_t d_int;       /* SwiGLU intermediate size */
+    int32_t vocab;
+    int32_t max_pos;     /* RoPE table length; position ids must be < max_pos */
+    int32_t qk_norm;     /* 1: per-head RMSNorm of q and k before RoPE (Qwen3) */
+    int32_t dtype;       /* radix_dtype: storage type of matrices and of GEMM operands */
+    float eps;           /* RMSNorm epsilon (inside the square root) */
+    float rope_base;
+} radix_model_config;
+
+/* Per-layer weights.  Matrices are [out, in] row-major as in y = W h (paper Eq. 5), stored
+ * in config.dtype.  RMSNorm gains are always fp32.  All pointers are device pointers. */
+typedef struct radix_layer_weights {
+    const float* g1;   /* [d]      pre-attention norm gain */
+    const void* wq;    /* [Hq*hd, d] */
+    const void* wk;    /* [Hkv*hd, d] */
+    const void* wv;    /* [Hkv*hd, d] */
+    const float* gq;   /* [hd]     q-norm gain (ignored when qk_norm == 0) */
+    const float* gk;   /* [hd]     k-norm gain */
+    const void* wo;    /* [d, Hq*hd] */
+    const float* g2;   /* [d]      post-attention norm gain */
+    const void* wg;    /* [d_int, d] gate */
+    const void* wu;    /* [d_int, d] up */
+    const void* wd;    /* [d, d_int] down */
+} radix_layer_weights;
+
+typedef struct radix_weights {
+    const void* embed;                       /* [vocab, d] in config.dtype (device) */
+    const float* gf;                         /* [d] final norm gain (device) */
+    const radix_layer_weights* layers_host;  /* HOST array of n_layers structs of device pointers */
+} radix_weights;
+
+typedef struct radix_model radix_model;      /* opaque */
+
+/* Options of the deduplicated forward (paper: Limitations, "Low-redundancy batches", and
+ * the radix_mlp_threshold setting of the end-to-end experiments). */
+typedef struct radix_fwd_opts {
+    float threshold;      /* deduplicate iff n_compact < threshold * N; 1.0 = whenever anything is shared */
+    int32_t force_dedup;  /* 1: always take the deduplicated path, whatever the threshold says */
+} radix_fwd_opts;
+
+/*
+ * radix_model_create - validate the configuration, build library-owned device copies of the
+ * weights in the layouts the kernels use (fused QKV matrix, gate/up interleaved) and the fp32
+ * RoPE cos/sin tables (angle p * base^(-2i/hd) evaluated in double precision; element i is
+ * paired with i + hd/2).  Synchronous.  The caller keeps ownership of the source weights and may
+ * free them once the call returns.  On error *out is NULL.
+ * radix_model_destroy frees everything the handle owns (NULL is accepted).
+ */
+int radix_model_create(const radix_model_config* config, const radix_weights* weights, radix_model** out);
+int radix_model_destroy(radix_model* model);
+
+/* Bytes of workspace radix_build_index needs for batches of up to max_B sequences. */
+int radix_index_workspace_bytes(int32_t max_B, size_t* bytes_out);
+
+/* Bytes of workspace the forward calls need for up to max_N tokens in up to max_B sequences.
+ * It is >= radix_index_workspace_bytes(max_B), so one buffer can serve both calls. */
+int radix_workspace_bytes(const radix_model* model, int32_t max_N, int32_t max_B, size_t* bytes_out);
+
+/*
+ * radix_build_index - prefix-trie index maps of a ragged batch (paper: "Trie Construction",
+ * "Gather and Scatter Kernels", appendix Algorithm 2 and its "Index semantics").
+ *
+ * Two original positions are the same trie node iff they sit at the same offset of their
+ * sequences and the (token id, position id) pairs of their whole causal histories agree.
+ *   I_gather[c]  (c < N') = smallest original position of compact node c; nodes are numbered
+ *                           in order of first occurrence, so I_gather is strictly increasing.
+ *   I_scatter[i] (i < N)  = compact node of original position i.
+ * The result is the unique one the sequential algorithm produces; maps are never padded.
+ *
+ *   tok          int32[N]    token ids, >= 0
+ *   pos          int32[N]    position ids, >= 0, or NULL for "offset inside the sequence"
+ *   cu_seqlens   int32[B+1]  cu_seqlens[0] = 0, non-decreasing, cu_seqlens[B] = N; empty sequences allowed
+ *   I_scatter    int32[N]    out
+ *   I_gather     int32[N]    out; only the first N' entries are written
+ *   n_compact_dev int32[1]   out (device), N'
+ *   n_compact_host           HOST pointer or NULL.  If given, the call waits for the stream,
+ *                            stores N' there and returns any device-data error.
+ *   ws, ws_bytes             workspace of at least radix_index_workspace_bytes(B)
+ * B = 0 or N = 0 is valid and yields N' = 0.
+ */
+int radix_build_index(const int32_t* tok, const int32_t* pos, const int32_t* cu_seqlens,
+                      int32_t B, int32_t N, int32_t* I_scatter, int32_t* I_gather,
+                      int32_t* n_compact_dev, int32_t* n_compact_host,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * radix_prefill_forward - deduplicated prefill (paper Algorithm 1 up to the final norm):
+ * gathers token and position ids to compact space, runs embedding, RMSNorm, Q/K/V projection,
+ * Q/K norm, RoPE, O projection, residual adds and the SwiGLU MLP on the n_compact unique rows,
+ * scatters Q/K/V to the full ragged layout for causal varlen attention, gathers the attention
+ * output back, and finally scatters the final-norm hidden state to all N rows.
+ *
+ *   tok, pos, cu_seqlens, B, N   as for radix_build_index (pos may be NULL)
+ *   max_seqlen                   >= longest sequence (host value; sizes the attention grid)
+ *   I_scatter, I_gather, n_compact   maps from radix_build_index for this batch (n_compact on the host)
+ *   opts                         NULL = {threshold 1.0, force_dedup 0}.  When the threshold says the
+ *                                batch is not worth deduplicating the no-dedup path runs instead.
+ *   out          float[N, d]     final-RMSNorm hidden state of every original token, ragged order
+ *   ws, ws_bytes                 workspace of at least radix_workspace_bytes(model, N, B)
+ * Asynchronous on `stream`.
+ */
+int radix_prefill_forward(const radix_model* model, const int32_t* tok, const int32_t* pos,
+                          const int32_t* cu_seqlens, int32_t B, int32_t N, int32_t max_seqlen,
+                          const int32_t* I_scatter, const int32_t* I_gather, int32_t n_compact,
+                          const radix_fwd_opts* opts, float* out,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * radix_prefill_forward_nodedup - the ordinary prefill over all N rows with the same kernels and
+ * no gather/scatter: the baseline the paper's speedups are measured against (Experiments,
+ * "RadixMLP disabled").  Arguments as above.
+ */
+int radix_prefill_forward_nodedup(const radix_model* model, const int32_t* tok, const int32_t* pos,
+                                  const int32_t* cu_seqlens, int32_t B, int32_t N, int32_t max_seqlen,
+                                  float* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * radix_index_select_rows - the gather/scatter operator itself (paper: Implementation Details,
+ * Gather(t, I)[j] = t[I[j]] and Scatter(t, I)[i] = t[I[i]]; both are row index-selects):
+ * dst[r, :] = src[idx[r], :] for r < n_rows.  row_bytes must be a multiple of 4; rows are
+ * contiguous.  Indices must lie in [0, n_src_rows); an index outside is clamped and recorded
+ * as RADIX_ERR_BAD_TOKEN in *status_dev when status_dev != NULL.
+ */
+int radix_index_select_rows(const void* src, int32_t n_src_rows, const int32_t* idx, int32_t n_rows,
+                            size_t row_bytes, void* dst, int32_t* status_dev, void* stream);
+
+/* Waits for `stream` and returns the device-data status recorded in the workspace by the most
+ * recent radix_build_index / radix_prefill_forward* call that used it (each call starts by
+ * clearing the status word; RADIX_OK if nothing was recorded). */
+int radix_device_status(void* ws, size_t ws_bytes, void* stream);
+
+/* Static description of a radix_status value. */
+const char* radix_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RADIXMLP_H */

@@ -1,0 +1,50 @@
+// Internal launcher declarations (one per kernel family).  Host code; every launcher enqueues
+// on `stream` and returns without synchronising.  Pointers are device pointers.
+#pragma once
+#include "common.h"
+
+// The first bytes of every workspace: int32 words {status, n_compact, ...}.
+#define RADIX_WS_HEADER_BYTES 256
+
+size_t radix_index_ws_bytes(int B);
+
+// ---- row operations (rowops.hip)
+// dst[r, :] = src[idx[r], :]; row_bytes % 4 == 0.  idx == nullptr copies rows 1:1.
+void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* idx, int n_rows,
+                              size_t row_bytes, void* dst, int32_t* status, hipStream_t stream);
+// Records RADIX_ERR_BAD_CU_SEQLENS in *status when cu is not 0 .. N non-decreasing with every
+// sequence <= max_seqlen.  (Kernels that index through cu clamp what they read from it.)
+void launch_validate_cu(const int32_t* cu, int B, int N, int max_seqlen, int32_t* status, hipStream_t stream);
+// pos_full[i] = i - cu[seq(i)]
+void launch_default_positions(const int32_t* cu, int B, int N, int32_t* pos_full, hipStream_t stream);
+// ids_c[j] = tok[Ig[j]], pos_c[j] = pos[Ig[j]]   (Ig == nullptr: identity)
+void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* Ig, int M, int N,
+                        int vocab, int max_pos, int32_t* ids_c, int32_t* pos_c, int32_t* status,
+                        hipStream_t stream);
+// h[j, :] = (float) E[ids_c[j], :]
+void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int d, float* h, hipStream_t stream);
+// out[j, :] = h[j, :] * rsqrt(mean(h[j]^2) + eps) * g   (out in `out_dtype`: RADIX_F32 / RADIX_BF16)
+void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
+                    hipStream_t stream);
+// In place on qkv[M, dq + 2 dkv]: per-head RMSNorm (optional) and RoPE of the q and k heads.
+void launch_qknorm_rope(void* qkv, int dtype, int M, int n_q_heads, int n_kv_heads, int hd, int qk_norm,
+                        const float* gq, const float* gk, float eps, const int32_t* pos_c,
+                        const float* cos_tab, const float* sin_tab, hipStream_t stream);
+
+// ---- GEMMs: C[M, Nout] = A[M, K] * W[Nout, K]^T with an epilogue
+enum GemmEpilogue {
+    EPI_STORE = 0,     // C stored in the activation dtype
+    EPI_RESIDUAL = 1,  // resid[M, Nout] (fp32) += C
+    EPI_SWIGLU = 2     // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
+};
+void launch_gemm_f32(const float* A, const float* W, int M, int Nout, int K, int epilogue, float* out_or_resid,
+                     hipStream_t stream);
+int launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int Nout, int K, int epilogue, void* out_or_resid,
+                     hipStream_t stream);
+
+// ---- causal varlen GQA attention on the full ragged layout.
+// qkv[N, dq + 2 dkv] rows hold q | k | v of one token; out[N, dq].
+void launch_attention_f32(const float* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
+                          int n_kv_heads, int hd, float* out, hipStream_t stream);
+int launch_attention_bf16(const bf16_t* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
+                          int n_kv_heads, int hd, bf16_t* out, hipStream_t stream);

@@ -1,0 +1,333 @@
+// Model handle (library-owned weight copies + RoPE tables), workspace layout and the host-side
+// launch sequence of the deduplicated / no-dedup prefill (paper: Algorithm 1).
+#include <math.h>
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "kernels.h"
+
+struct radix_layer_dev {
+    const float *g1, *g2, *gq, *gk;
+    const void *wqkv;   // [dq + 2 dkv, d]  rows: q heads, k heads, v heads
+    const void *wo;     // [d, dq]
+    const void *wgu;    // [2 d_int, d]     gate/up interleaved in blocks of 32 rows
+    const void *wd;     // [d, d_int]
+};
+
+struct radix_model {
+    radix_model_config cfg;
+    char* blob = nullptr;          // one device allocation holding everything below
+    const void* embed = nullptr;
+    const float* gf = nullptr;
+    const float* cos_tab = nullptr;
+    const float* sin_tab = nullptr;
+    std::vector<radix_layer_dev> layers;
+};
+
+namespace {
+
+__global__ void interleave_gate_up_kernel(const uint4* __restrict__ wg, const uint4* __restrict__ wu, int d_int,
+                                          int row_vecs, uint4* __restrict__ dst) {
+    const int R = blockIdx.x;                  // destination row in [0, 2 d_int)
+    const int t = R >> 6, w = R & 63;
+    const uint4* src = (w < 32 ? wg : wu) + (size_t)(32 * t + (w & 31)) * row_vecs;
+    uint4* d = dst + (size_t)R * row_vecs;
+    for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) d[c] = src[c];
+}
+
+__global__ void clear_status_kernel(int32_t* hdr) { hdr[0] = 0; }
+
+size_t esize(int dtype) { return dtype == RADIX_BF16 ? 2 : 4; }
+
+struct WsLayout {
+    size_t pos_full, ids_c, pos_c, h, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
+};
+
+WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
+    const size_t es = esize(c.dtype);
+    const size_t dq = (size_t)c.n_q_heads * c.head_dim, dkv = (size_t)c.n_kv_heads * c.head_dim;
+    const size_t row = dq + 2 * dkv;
+    const size_t M = N;                       // worst case: nothing is shared
+    size_t off = radix_index_ws_bytes((int)B);
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 1, 256); return o; };
+    WsLayout L;
+    L.pos_full = take(N * 4);
+    L.ids_c = take(M * 4);
+    L.pos_c = take(M * 4);
+    L.h = take(M * c.d * 4);
+    L.a = take(M * c.d * es);
+    L.qkv = take(M * row * es);
+    L.qkv_full = take(N * row * es);
+    L.attn_full = take(N * dq * es);
+    L.attn_c = take(M * dq * es);
+    L.mlp = take(M * (size_t)c.d_int * es);
+    L.ynorm = take(M * c.d * 4);
+    L.total = off;
+    return L;
+}
+
+int check_config(const radix_model_config& c) {
+    if (c.n_layers <= 0 || c.d <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.head_dim <= 0 || c.d_int <= 0 ||
+        c.vocab <= 0 || c.max_pos <= 0)
+        return RADIX_ERR_BAD_CONFIG;
+    if (c.n_q_heads % c.n_kv_heads != 0) return RADIX_ERR_BAD_CONFIG;
+    if (!(c.eps >= 0.f) || !(c.rope_base > 0.f)) return RADIX_ERR_BAD_CONFIG;
+    if (c.dtype != RADIX_F32 && c.dtype != RADIX_BF16) return RADIX_ERR_UNSUPPORTED;
+    if (c.head_dim % 2 != 0 || c.head_dim > 128) return RADIX_ERR_UNSUPPORTED;
+    if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
+    if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
+    if (c.dtype == RADIX_BF16) {
+        // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 64 and every
+        // GEMM output width a multiple of 128
+        const int dq = c.n_q_heads * c.head_dim, dkv = c.n_kv_heads * c.head_dim;
+        if (c.head_dim != 128) return RADIX_ERR_UNSUPPORTED;
+        if (c.d % 128 != 0 || c.d_int % 64 != 0 || (dq + 2 * dkv) % 128 != 0) return RADIX_ERR_UNSUPPORTED;
+    }
+    return RADIX_OK;
+}
+
+}  // namespace
+
+extern "C" int radix_model_create(const radix_model_config* config, const radix_weights* weights, radix_model** out) {
+    if (!out) return RADIX_ERR_NULL_POINTER;
+    *out = nullptr;
+    if (!config || !weights) return RADIX_ERR_NULL_POINTER;
+    const radix_model_config c = *config;
+    int rc = check_config(c);
+    if (rc != RADIX_OK) return rc;
+    if (!weights->embed || !weights->gf || !weights->layers_host) return RADIX_ERR_NULL_POINTER;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const radix_layer_weights& w = weights->layers_host[l];
+        if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wg || !w.wu || !w.wd) return RADIX_ERR_NULL_POINTER;
+        if (c.qk_norm && (!w.gq || !w.gk)) return RADIX_ERR_NULL_POINTER;
+    }
+    const size_t es = esize(c.dtype);
+    const size_t d = c.d, hd = c.head_dim, dq = (size_t)c.n_q_heads * hd, dkv = (size_t)c.n_kv_heads * hd;
+    const size_t di = c.d_int, half = hd / 2;
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    const size_t o_embed = take((size_t)c.vocab * d * es), o_gf = take(d * 4);
+    const size_t o_cos = take((size_t)c.max_pos * half * 4), o_sin = take((size_t)c.max_pos * half * 4);
+    struct LO { size_t g1, g2, gq, gk, wqkv, wo, wgu, wd; };
+    std::vector<LO> lo(c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        lo[l].g1 = take(d * 4); lo[l].g2 = take(d * 4); lo[l].gq = take(hd * 4); lo[l].gk = take(hd * 4);
+        lo[l].wqkv = take((dq + 2 * dkv) * d * es);
+        lo[l].wo = take(d * dq * es);
+        lo[l].wgu = take(2 * di * d * es);
+        lo[l].wd = take(d * di * es);
+    }
+    radix_model* m = new (std::nothrow) radix_model();
+    if (!m) return RADIX_ERR_HIP;
+    m->cfg = c;
+    if (hipMalloc((void**)&m->blob, off) != hipSuccess) { delete m; return RADIX_ERR_HIP; }
+    char* b = m->blob;
+    bool ok = true;
+    auto d2d = [&](size_t dst, const void* src, size_t bytes) {
+        if (ok && hipMemcpyAsync(b + dst, src, bytes, hipMemcpyDeviceToDevice, 0) != hipSuccess) ok = false;
+    };
+    d2d(o_embed, weights->embed, (size_t)c.vocab * d * es);
+    d2d(o_gf, weights->gf, d * 4);
+    {
+        std::vector<float> ct((size_t)c.max_pos * half), st((size_t)c.max_pos * half);
+        for (size_t i = 0; i < half; ++i) {
+            const double theta = pow((double)c.rope_base, -2.0 * (double)i / (double)hd);
+            for (size_t p = 0; p < (size_t)c.max_pos; ++p) {
+                const double ang = (double)p * theta;
+                ct[p * half + i] = (float)cos(ang);
+                st[p * half + i] = (float)sin(ang);
+            }
+        }
+        if (hipMemcpy(b + o_cos, ct.data(), ct.size() * 4, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+        if (hipMemcpy(b + o_sin, st.data(), st.size() * 4, hipMemcpyHostToDevice) != hipSuccess) ok = false;
+    }
+    m->embed = b + o_embed;
+    m->gf = (const float*)(b + o_gf);
+    m->cos_tab = (const float*)(b + o_cos);
+    m->sin_tab = (const float*)(b + o_sin);
+    m->layers.resize(c.n_layers);
+    const int row_vecs = (int)(d * es / 16);
+    for (int l = 0; l < c.n_layers && ok; ++l) {
+        const radix_layer_weights& w = weights->layers_host[l];
+        d2d(lo[l].g1, w.g1, d * 4);
+        d2d(lo[l].g2, w.g2, d * 4);
+        if (c.qk_norm) { d2d(lo[l].gq, w.gq, hd * 4); d2d(lo[l].gk, w.gk, hd * 4); }
+        d2d(lo[l].wqkv, w.wq, dq * d * es);
+        d2d(lo[l].wqkv + dq * d * es, w.wk, dkv * d * es);
+        d2d(lo[l].wqkv + (dq + dkv) * d * es, w.wv, dkv * d * es);
+        d2d(lo[l].wo, w.wo, d * dq * es);
+        d2d(lo[l].wd, w.wd, d * di * es);
+        if ((((uintptr_t)w.wg | (uintptr_t)w.wu) & 15) != 0) { ok = false; rc = RADIX_ERR_MISALIGNED; break; }
+        hipLaunchKernelGGL(interleave_gate_up_kernel, dim3((unsigned)(2 * di)), dim3(256), 0, 0, (const uint4*)w.wg,
+                           (const uint4*)w.wu, (int)di, row_vecs, (uint4*)(b + lo[l].wgu));
+        radix_layer_dev& L = m->layers[l];
+        L.g1 = (const float*)(b + lo[l].g1); L.g2 = (const float*)(b + lo[l].g2);
+        L.gq = (const float*)(b + lo[l].gq); L.gk = (const float*)(b + lo[l].gk);
+        L.wqkv = b + lo[l].wqkv; L.wo = b + lo[l].wo; L.wgu = b + lo[l].wgu; L.wd = b + lo[l].wd;
+    }
+    if (ok && hipDeviceSynchronize() != hipSuccess) ok = false;
+    if (ok && hipGetLastError() != hipSuccess) ok = false;
+    if (!ok) {
+        (void)hipFree(m->blob);
+        delete m;
+        return rc != RADIX_OK ? rc : RADIX_ERR_HIP;
+    }
+    *out = m;
+    return RADIX_OK;
+}
+
+extern "C" int radix_model_destroy(radix_model* model) {
+    if (!model) return RADIX_OK;
+    hipError_t e = hipFree(model->blob);
+    delete model;
+    return e == hipSuccess ? RADIX_OK : RADIX_ERR_HIP;
+}
+
+extern "C" int radix_workspace_bytes(const radix_model* model, int32_t max_N, int32_t max_B, size_t* bytes_out) {
+    if (!model || !bytes_out) return RADIX_ERR_NULL_POINTER;
+    if (max_N < 0 || max_B < 0) return RADIX_ERR_BAD_SIZE;
+    *bytes_out = ws_layout(model->cfg, (size_t)max_N, (size_t)max_B).total;
+    return RADIX_OK;
+}
+
+extern "C" int radix_device_status(void* ws, size_t ws_bytes, void* stream) {
+    if (!ws) return RADIX_ERR_NULL_POINTER;
+    if (ws_bytes < RADIX_WS_HEADER_BYTES) return RADIX_ERR_WORKSPACE_TOO_SMALL;
+    int32_t st = 0;
+    HIP_TRY(hipMemcpyAsync(&st, ws, sizeof(st), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return st;
+}
+
+namespace {
+
+int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* pos, const int32_t* cu, int B, int N,
+                 int max_seqlen, const int32_t* Is, const int32_t* Ig, int M, bool dedup, float* out, void* ws,
+                 size_t ws_bytes, hipStream_t stream) {
+    const radix_model_config& c = model->cfg;
+    const WsLayout L = ws_layout(c, (size_t)N, (size_t)B);
+    if (ws_bytes < L.total) return RADIX_ERR_WORKSPACE_TOO_SMALL;
+    char* w = (char*)ws;
+    int32_t* hdr = (int32_t*)w;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, stream, hdr);
+    if (N == 0) { HIP_TRY(hipGetLastError()); return RADIX_OK; }
+    launch_validate_cu(cu, B, N, max_seqlen, hdr, stream);
+
+    const int dt = c.dtype;
+    const size_t es = esize(dt);
+    const int d = c.d, hd = c.head_dim, dq = c.n_q_heads * hd, dkv = c.n_kv_heads * hd, row = dq + 2 * dkv;
+    int32_t* pos_full = (int32_t*)(w + L.pos_full);
+    int32_t* ids_c = (int32_t*)(w + L.ids_c);
+    int32_t* pos_c = (int32_t*)(w + L.pos_c);
+    float* h = (float*)(w + L.h);
+    void* a = w + L.a;
+    void* qkv = w + L.qkv;
+    void* qkv_full = dedup ? (void*)(w + L.qkv_full) : qkv;
+    void* attn_full = w + L.attn_full;
+    void* attn_c = dedup ? (void*)(w + L.attn_c) : attn_full;
+    void* mlp = w + L.mlp;
+    float* ynorm = (float*)(w + L.ynorm);
+
+    // Token compaction: positions and ids of the representatives (Algorithm 1, first block)
+    if (!pos) {
+        launch_default_positions(cu, B, N, pos_full, stream);
+        pos = pos_full;
+    }
+    launch_compact_ids(tok, pos, dedup ? Ig : nullptr, M, N, c.vocab, c.max_pos, ids_c, pos_c, hdr, stream);
+    launch_embed(model->embed, dt, ids_c, M, d, h, stream);
+
+    auto gemm = [&](const void* A, const void* W, int Nout, int K, int epi, void* o) -> int {
+        if (dt == RADIX_BF16) return launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, Nout, K, epi, o, stream);
+        launch_gemm_f32((const float*)A, (const float*)W, M, Nout, K, epi, (float*)o, stream);
+        return RADIX_OK;
+    };
+
+    int rc = RADIX_OK;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const radix_layer_dev& Lw = model->layers[l];
+        launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
+        if ((rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv)) != RADIX_OK) return rc;
+        launch_qknorm_rope(qkv, dt, M, c.n_q_heads, c.n_kv_heads, hd, c.qk_norm, Lw.gq, Lw.gk, c.eps, pos_c,
+                           model->cos_tab, model->sin_tab, stream);
+        if (dedup)   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
+            launch_index_select_rows(qkv, M, Is, N, (size_t)row * es, qkv_full, hdr, stream);
+        if (dt == RADIX_BF16) {
+            rc = launch_attention_bf16((const bf16_t*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,
+                                       (bf16_t*)attn_full, stream);
+            if (rc != RADIX_OK) return rc;
+        } else {
+            launch_attention_f32((const float*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,
+                                 (float*)attn_full, stream);
+        }
+        if (dedup)   // Gather(a)
+            launch_index_select_rows(attn_full, N, Ig, M, (size_t)dq * es, attn_c, hdr, stream);
+        if ((rc = gemm(attn_c, Lw.wo, d, dq, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+        launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
+        if ((rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp)) != RADIX_OK) return rc;
+        if ((rc = gemm(mlp, Lw.wd, d, c.d_int, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+    }
+    if (dedup) {
+        launch_rmsnorm(h, model->gf, M, d, c.eps, ynorm, RADIX_F32, stream);
+        launch_index_select_rows(ynorm, M, Is, N, (size_t)d * 4, out, hdr, stream);   // expand for output
+    } else {
+        launch_rmsnorm(h, model->gf, M, d, c.eps, out, RADIX_F32, stream);
+    }
+    HIP_TRY(hipGetLastError());
+    return RADIX_OK;
+}
+
+int check_common(const radix_model* model, const int32_t* tok, const int32_t* cu, int B, int N, int max_seqlen,
+                 const float* out, const void* ws) {
+    if (!model || !cu || !ws) return RADIX_ERR_NULL_POINTER;
+    if (B < 0 || N < 0 || max_seqlen < 0) return RADIX_ERR_BAD_SIZE;
+    if (N > 0 && (!tok || !out)) return RADIX_ERR_NULL_POINTER;
+    if (N > 0 && (B == 0 || max_seqlen == 0)) return RADIX_ERR_BAD_SIZE;
+    if (B > 65535) return RADIX_ERR_UNSUPPORTED;
+    if ((((uintptr_t)ws) & 255) != 0 || (((uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
+    return RADIX_OK;
+}
+
+}  // namespace
+
+extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* tok, const int32_t* pos,
+                                     const int32_t* cu_seqlens, int32_t B, int32_t N, int32_t max_seqlen,
+                                     const int32_t* I_scatter, const int32_t* I_gather, int32_t n_compact,
+                                     const radix_fwd_opts* opts, float* out, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_common(model, tok, cu_seqlens, B, N, max_seqlen, out, ws);
+    if (rc != RADIX_OK) return rc;
+    if (n_compact < 0 || n_compact > N || (N > 0 && n_compact == 0)) return RADIX_ERR_BAD_SIZE;
+    if (N > 0 && (!I_scatter || !I_gather)) return RADIX_ERR_NULL_POINTER;
+    const float threshold = opts ? opts->threshold : 1.0f;
+    const bool force = opts ? opts->force_dedup != 0 : false;
+    const bool dedup = force || ((double)n_compact < (double)threshold * (double)N);
+    if (!dedup) n_compact = N;
+    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, I_scatter, I_gather, n_compact, dedup, out, ws,
+                        ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int32_t* tok, const int32_t* pos,
+                                             const int32_t* cu_seqlens, int32_t B, int32_t N, int32_t max_seqlen,
+                                             float* out, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_common(model, tok, cu_seqlens, B, N, max_seqlen, out, ws);
+    if (rc != RADIX_OK) return rc;
+    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, out, ws, ws_bytes,
+                        (hipStream_t)stream);
+}
+
+extern "C" const char* radix_status_string(int status) {
+    switch (status) {
+        case RADIX_OK: return "ok";
+        case RADIX_ERR_NULL_POINTER: return "null pointer argument";
+        case RADIX_ERR_BAD_SIZE: return "bad size argument";
+        case RADIX_ERR_UNSUPPORTED: return "unsupported shape, head_dim or dtype";
+        case RADIX_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case RADIX_ERR_MISALIGNED: return "misaligned pointer";
+        case RADIX_ERR_BAD_CU_SEQLENS: return "cu_seqlens is not a non-decreasing array from 0 to N";
+        case RADIX_ERR_BAD_TOKEN: return "token id, position id or index out of range";
+        case RADIX_ERR_HIP: return "HIP runtime error";
+        case RADIX_ERR_BAD_CONFIG: return "inconsistent model configuration";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,206 @@
+// Row-wise, HBM-bound kernels of the compact-space pipeline: gather/scatter (row index-select),
+// id/position compaction, embedding lookup, RMSNorm and Q/K-norm + RoPE.
+// (Paper: Algorithm 1 "Token Compaction", "Embedding (Compact Space)", "Position Encoding";
+//  Implementation Details for the Gather / Scatter operators.)
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+// ------------------------------------------------------------------ index-select of rows
+// One wavefront per destination row, 16-byte accesses when the row allows it.  Scatter
+// (N' -> N rows) and gather (N -> N' rows) are the same kernel with different index maps.
+template <typename V>
+__global__ __launch_bounds__(256) void index_select_kernel(const V* __restrict__ src, int n_src_rows,
+                                                           const int32_t* __restrict__ idx, int n_rows,
+                                                           int row_vecs, V* __restrict__ dst, int32_t* status) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= n_rows) return;
+    int s = idx ? idx[row] : row;
+    if (s < 0 || s >= n_src_rows) {
+        if (lane == 0) set_status(status, RADIX_ERR_BAD_TOKEN);
+        s = s < 0 ? 0 : n_src_rows - 1;
+    }
+    const V* sp = src + (size_t)s * row_vecs;
+    V* dp = dst + (size_t)row * row_vecs;
+    for (int c = lane; c < row_vecs; c += 64) dp[c] = sp[c];
+}
+
+// cu_seqlens must run from 0 to N without decreasing and no sequence may exceed max_seqlen.
+__global__ void validate_cu_kernel(const int32_t* __restrict__ cu, int B, int N, int max_seqlen, int32_t* status) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > B) return;
+    const int c = cu[i];
+    bool bad = c < 0 || c > N || (i == 0 && c != 0) || (i == B && c != N);
+    if (i < B) {
+        const int len = cu[i + 1] - c;
+        bad = bad || len < 0 || len > max_seqlen;
+    }
+    if (bad) set_status(status, RADIX_ERR_BAD_CU_SEQLENS);
+}
+
+__global__ void default_positions_kernel(const int32_t* __restrict__ cu, int B, int N, int32_t* __restrict__ pos) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= N) return;
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (cu[mid + 1] > j) hi = mid; else lo = mid + 1;
+    }
+    pos[j] = j - cu[lo];
+}
+
+__global__ void compact_ids_kernel(const int32_t* __restrict__ tok, const int32_t* __restrict__ pos,
+                                   const int32_t* __restrict__ Ig, int M, int N, int vocab, int max_pos,
+                                   int32_t* __restrict__ ids_c, int32_t* __restrict__ pos_c, int32_t* status) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= M) return;
+    int i = Ig ? Ig[j] : j;
+    if (i < 0 || i >= N) { set_status(status, RADIX_ERR_BAD_TOKEN); i = 0; }
+    int t = tok[i], p = pos[i];
+    if (t < 0 || t >= vocab) { set_status(status, RADIX_ERR_BAD_TOKEN); t = 0; }
+    if (p < 0 || p >= max_pos) { set_status(status, RADIX_ERR_BAD_TOKEN); p = 0; }
+    ids_c[j] = t;
+    pos_c[j] = p;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ ids,
+                                                    int M, int d, float* __restrict__ h) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const T* e = E + (size_t)ids[row] * d;
+    float* o = h + (size_t)row * d;
+    for (int c = lane; c < d; c += 64) o[c] = to_f32<T>(e[c]);
+}
+
+// One wavefront per row; the row is read twice (second read hits L2/L1).
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ g,
+                                                      int M, int d, float eps, T* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const float* x = h + (size_t)row * d;
+    float ss = 0.f;
+    for (int c = lane; c < d; c += 64) { float v = x[c]; ss += v * v; }
+    ss = wave_sum(ss);
+    const float r = 1.0f / sqrtf(ss / (float)d + eps);
+    T* o = out + (size_t)row * d;
+    for (int c = lane; c < d; c += 64) o[c] = from_f32<T>(x[c] * r * g[c]);
+}
+
+// One wavefront per (row, head); lane i < hd/2 owns the rotary pair (i, i + hd/2).
+template <typename T>
+__global__ __launch_bounds__(256) void qknorm_rope_kernel(T* __restrict__ qkv, int M, int n_q_heads, int n_kv_heads,
+                                                          int hd, int qk_norm, const float* __restrict__ gq,
+                                                          const float* __restrict__ gk, float eps,
+                                                          const int32_t* __restrict__ pos_c,
+                                                          const float* __restrict__ cos_tab,
+                                                          const float* __restrict__ sin_tab) {
+    const int lane = threadIdx.x & 63;
+    const int heads = n_q_heads + n_kv_heads;
+    const long long item = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (item >= (long long)M * heads) return;
+    const int row = (int)(item / heads), head = (int)(item % heads);
+    const int half = hd >> 1;
+    const int row_elems = (n_q_heads + 2 * n_kv_heads) * hd;
+    T* x = qkv + (size_t)row * row_elems + (size_t)head * hd;   // q heads then k heads are contiguous
+    const float* g = head < n_q_heads ? gq : gk;
+    const bool act = lane < half;
+    float a = act ? to_f32<T>(x[lane]) : 0.f;
+    float b = act ? to_f32<T>(x[lane + half]) : 0.f;
+    if (qk_norm) {
+        float ss = wave_sum(a * a + b * b);
+        const float r = 1.0f / sqrtf(ss / (float)hd + eps);
+        if (act) { a = a * r * g[lane]; b = b * r * g[lane + half]; }
+    }
+    if (act) {
+        const int p = pos_c[row];
+        const float c = cos_tab[(size_t)p * half + lane], s = sin_tab[(size_t)p * half + lane];
+        x[lane] = from_f32<T>(a * c - b * s);
+        x[lane + half] = from_f32<T>(b * c + a * s);
+    }
+}
+
+}  // namespace
+
+void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* idx, int n_rows, size_t row_bytes,
+                              void* dst, int32_t* status, hipStream_t stream) {
+    if (n_rows <= 0 || row_bytes == 0) return;
+    const int rows_per_block = 4;
+    dim3 grid(ceil_div(n_rows, rows_per_block)), block(256);
+    const bool al16 = (row_bytes % 16 == 0) && (((uintptr_t)src | (uintptr_t)dst) % 16 == 0);
+    if (al16) {
+        hipLaunchKernelGGL(index_select_kernel<uint4>, grid, block, 0, stream, (const uint4*)src, n_src_rows, idx,
+                           n_rows, (int)(row_bytes / 16), (uint4*)dst, status);
+    } else {
+        hipLaunchKernelGGL(index_select_kernel<uint32_t>, grid, block, 0, stream, (const uint32_t*)src, n_src_rows,
+                           idx, n_rows, (int)(row_bytes / 4), (uint32_t*)dst, status);
+    }
+}
+
+void launch_validate_cu(const int32_t* cu, int B, int N, int max_seqlen, int32_t* status, hipStream_t stream) {
+    hipLaunchKernelGGL(validate_cu_kernel, dim3(ceil_div(B + 1, 256)), dim3(256), 0, stream, cu, B, N, max_seqlen,
+                       status);
+}
+
+void launch_default_positions(const int32_t* cu, int B, int N, int32_t* pos_full, hipStream_t stream) {
+    if (N <= 0) return;
+    hipLaunchKernelGGL(default_positions_kernel, dim3(ceil_div(N, 256)), dim3(256), 0, stream, cu, B, N, pos_full);
+}
+
+void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* Ig, int M, int N, int vocab,
+                        int max_pos, int32_t* ids_c, int32_t* pos_c, int32_t* status, hipStream_t stream) {
+    if (M <= 0) return;
+    hipLaunchKernelGGL(compact_ids_kernel, dim3(ceil_div(M, 256)), dim3(256), 0, stream, tok, pos, Ig, M, N, vocab,
+                       max_pos, ids_c, pos_c, status);
+}
+
+void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int d, float* h, hipStream_t stream) {
+    if (M <= 0) return;
+    dim3 grid(ceil_div(M, 4)), block(256);
+    if (dtype == RADIX_BF16)
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, grid, block, 0, stream, (const bf16_t*)embed, ids_c, M, d, h);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, grid, block, 0, stream, (const float*)embed, ids_c, M, d, h);
+}
+
+void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
+                    hipStream_t stream) {
+    if (M <= 0) return;
+    dim3 grid(ceil_div(M, 4)), block(256);
+    if (out_dtype == RADIX_BF16)
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, grid, block, 0, stream, h, g, M, d, eps, (bf16_t*)out);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, grid, block, 0, stream, h, g, M, d, eps, (float*)out);
+}
+
+void launch_qknorm_rope(void* qkv, int dtype, int M, int n_q_heads, int n_kv_heads, int hd, int qk_norm,
+                        const float* gq, const float* gk, float eps, const int32_t* pos_c, const float* cos_tab,
+                        const float* sin_tab, hipStream_t stream) {
+    if (M <= 0) return;
+    const long long items = (long long)M * (n_q_heads + n_kv_heads);
+    dim3 grid((unsigned)((items + 3) / 4)), block(256);
+    if (dtype == RADIX_BF16)
+        hipLaunchKernelGGL(qknorm_rope_kernel<bf16_t>, grid, block, 0, stream, (bf16_t*)qkv, M, n_q_heads, n_kv_heads,
+                           hd, qk_norm, gq, gk, eps, pos_c, cos_tab, sin_tab);
+    else
+        hipLaunchKernelGGL(qknorm_rope_kernel<float>, grid, block, 0, stream, (float*)qkv, M, n_q_heads, n_kv_heads,
+                           hd, qk_norm, gq, gk, eps, pos_c, cos_tab, sin_tab);
+}
+
+extern "C" int radix_index_select_rows(const void* src, int32_t n_src_rows, const int32_t* idx, int32_t n_rows,
+                                       size_t row_bytes, void* dst, int32_t* status_dev, void* stream) {
+    if (n_rows < 0 || n_src_rows < 0) return RADIX_ERR_BAD_SIZE;
+    if (n_rows == 0) return RADIX_OK;
+    if (!src || !idx || !dst) return RADIX_ERR_NULL_POINTER;
+    if (n_src_rows == 0) return RADIX_ERR_BAD_SIZE;
+    if (row_bytes % 4 != 0) return RADIX_ERR_MISALIGNED;
+    if ((((uintptr_t)src | (uintptr_t)dst) & 3) != 0) return RADIX_ERR_MISALIGNED;
+    launch_index_select_rows(src, n_src_rows, idx, n_rows, row_bytes, dst, status_dev, (hipStream_t)stream);
+    HIP_TRY(hipGetLastError());
+    return RADIX_OK;
+}

@@ -1,0 +1,163 @@
+"""GPU parity of the deduplicated / no-dedup prefill against the fp64 no-dedup oracle.
+
+Tolerances (max |err| over all outputs, relative to the RMS of the oracle's output):
+  fp32 configuration: 1e-4; bf16 configurations: 2e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_15013_amd import binding, harness, synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+
+
+def run_all(weights, batch, pos=None, **kw):
+    model = harness.upload_model(weights)
+    try:
+        run = harness.Runner(model, batch.N, batch.B)
+        tok, cu = harness.upload_batch(batch)
+        pos_t = None if pos is None else torch.from_numpy(np.asarray(pos, dtype=np.int32)).cuda()
+        maps = run.build_index(tok, cu, pos_t)
+        y = run.forward(tok, cu, batch.max_seqlen, maps, pos=pos_t, **kw).cpu().numpy()
+        assert run.status() == 0
+        y_nd = run.forward_nodedup(tok, cu, batch.max_seqlen, pos=pos_t).cpu().numpy()
+        assert run.status() == 0
+        return y, y_nd, maps[3]
+    finally:
+        model.close()
+
+
+def test_c1_fp32_full():
+    b = synth.make_batch("C1")
+    w = synth.make_weights("C1")
+    y, y_nd, n_c = run_all(w, b)
+    assert n_c == 160
+    ref = U.oracle_rows(w, b)
+    assert U.rel_err(y_nd, ref) <= TOL_F32
+    assert U.rel_err(y, ref) <= TOL_F32
+    # row-invariant kernels: the deduplicated pass reproduces the no-dedup pass bit for bit
+    assert np.array_equal(y, y_nd)
+
+
+@pytest.mark.parametrize("pattern", synth.SHARING_PATTERNS)
+def test_fp32_sharing_patterns(pattern):
+    cfg = synth.ModelConfig("val", 2, 256, 4, 2, 64, 512, 1024, "f32", max_pos=64)   # the paper's validation scale
+    w = synth.SynthWeights(cfg, 21)
+    b = synth.sharing_pattern(pattern, 11)
+    y, y_nd, n_c = run_all(w, b, force_dedup=True)
+    ref = U.oracle_rows(w, b)
+    assert U.rel_err(y, ref) <= TOL_F32 and U.rel_err(y_nd, ref) <= TOL_F32
+    assert np.array_equal(y, y_nd)
+
+
+def test_fp32_ragged_lengths_gqa4_hd128_explicit_positions():
+    cfg = synth.ModelConfig("f32b", 2, 192, 8, 2, 128, 160, 300, "f32", max_pos=512, rope_base=1e4)
+    w = synth.SynthWeights(cfg, 22)
+    b = synth.multilevel_batch(5, 12, 70, 3, 9, 1, 130, cfg.vocab)
+    pos = np.concatenate([np.arange(n) + 3 for n in np.diff(b.cu_seqlens)])
+    y, y_nd, n_c = run_all(w, b, pos=pos)
+    ref = U.oracle_rows(w, b, pos=pos)
+    assert U.rel_err(y, ref) <= TOL_F32 and U.rel_err(y_nd, ref) <= TOL_F32
+    assert np.array_equal(y, y_nd)
+
+
+def test_fp32_no_qk_norm():
+    cfg = synth.ModelConfig("f32c", 1, 64, 2, 2, 32, 96, 100, "f32", max_pos=64, qk_norm=False)
+    w = synth.SynthWeights(cfg, 23)
+    b = synth.shared_prefix_batch(3, 5, 7, 1, 20, cfg.vocab)
+    y, y_nd, _ = run_all(w, b)
+    ref = U.oracle_rows(w, b)
+    assert U.rel_err(y, ref) <= TOL_F32 and np.array_equal(y, y_nd)
+
+
+SMALL_BF16 = synth.ModelConfig("bf16s", 3, 256, 4, 2, 128, 320, 2000, "bf16", max_pos=1024)
+
+
+def test_bf16_small_model_several_tiles_and_ragged_tail():
+    # M = N' is not a multiple of any tile size; sequences span several attention tiles
+    w = synth.SynthWeights(SMALL_BF16, 31)
+    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab)
+    y, y_nd, n_c = run_all(w, b)
+    assert n_c == b.expected_n_compact and n_c % 32 != 0
+    ref = U.oracle_rows(w, b)
+    assert U.rel_err(y_nd, ref) <= TOL_BF16
+    assert U.rel_err(y, ref) <= TOL_BF16
+    assert np.array_equal(y, y_nd)
+
+
+def test_bf16_single_sequence_and_tiny_batches():
+    w = synth.SynthWeights(SMALL_BF16, 32)
+    for b in (synth.shared_prefix_batch(1, 1, 0, 1, 1, 2000), synth.shared_prefix_batch(2, 1, 5, 200, 200, 2000),
+              synth.shared_prefix_batch(3, 3, 1, 1, 3, 2000)):
+        y, y_nd, _ = run_all(w, b, force_dedup=True)
+        ref = U.oracle_rows(w, b)
+        assert U.rel_err(y, ref) <= TOL_BF16 and np.array_equal(y, y_nd)
+
+
+def test_threshold_gating_and_forced_dedup():
+    w = synth.SynthWeights(SMALL_BF16, 33)
+    b = synth.shared_prefix_batch(4, 6, 20, 5, 30, 2000)
+    model = harness.upload_model(w)
+    run = harness.Runner(model, b.N, b.B)
+    tok, cu = harness.upload_batch(b)
+    maps = run.build_index(tok, cu)
+    y_on = run.forward(tok, cu, b.max_seqlen, maps).cpu()
+    y_off = run.forward(tok, cu, b.max_seqlen, maps, threshold=0.0).cpu()      # gated off: plain path
+    y_forced = run.forward(tok, cu, b.max_seqlen, maps, threshold=0.0, force_dedup=True).cpu()
+    y_nd = run.forward_nodedup(tok, cu, b.max_seqlen).cpu()
+    assert torch.equal(y_off, y_nd) and torch.equal(y_on, y_nd) and torch.equal(y_forced, y_nd)
+    model.close()
+
+
+def test_empty_batch_and_bad_inputs():
+    w = synth.SynthWeights(SMALL_BF16, 34)
+    model = harness.upload_model(w)
+    run = harness.Runner(model, 64, 4)
+    cu0 = torch.zeros(3, dtype=torch.int32, device="cuda")
+    tok0 = torch.zeros(0, dtype=torch.int32, device="cuda")
+    maps = run.build_index(tok0, cu0)
+    assert maps[3] == 0
+    out = run.forward(tok0, cu0, 0, maps)
+    assert out.shape == (0, SMALL_BF16.d)
+    # token id beyond the vocabulary: reported through the status word, no fault
+    tok = torch.tensor([1, 2, 5000, 4], dtype=torch.int32, device="cuda")
+    cu = torch.tensor([0, 2, 4], dtype=torch.int32, device="cuda")
+    run.forward_nodedup(tok, cu, 2)
+    assert run.status() == -7
+    # malformed cu_seqlens in the forward: reported, no fault
+    tok = torch.tensor([1, 2, 3, 4], dtype=torch.int32, device="cuda")
+    run.forward_nodedup(tok, torch.tensor([0, 3, 2], dtype=torch.int32, device="cuda"), 4)
+    assert run.status() == -6
+    run.forward_nodedup(tok, cu, 2)
+    assert run.status() == 0
+    # workspace too small is a host-side error
+    small = binding.alloc_workspace(1024)
+    with pytest.raises(binding.RadixError) as e:
+        binding.radix_prefill_forward_nodedup(model, tok, None, cu, 2, small)
+    assert e.value.code == -4
+    model.close()
+
+
+def _sampled_parity(key, sequences, tol=TOL_BF16):
+    """Full-size batch on the GPU in the benchmark's launch configuration; the oracle computes
+    whole sampled sequences (the no-dedup pass is independent per sequence)."""
+    b = synth.make_batch(key)
+    w = synth.make_weights(key)
+    y, y_nd, n_c = run_all(w, b, force_dedup=True)
+    assert n_c == b.expected_n_compact
+    rows = U.rows_of(b, sequences)
+    ref = U.oracle_rows(w, b, sequences=sequences)
+    e_d, e_n = U.rel_err(y[rows], ref), U.rel_err(y_nd[rows], ref)
+    print(f"{key}: N={b.N} N'={n_c} sampled rows={len(rows)} err dedup={e_d:.3e} nodedup={e_n:.3e}")
+    assert e_d <= tol and e_n <= tol
+    assert np.array_equal(y, y_nd)          # every row of the full batch, not just the sample
+    assert np.all(np.isfinite(y))
+
+
+def test_c2_full_size_sampled_sequences():
+    _sampled_parity("C2", [0, 17, 40, 63])
