@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the deduplicated prefill hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic batch that is already resident in
+HBM: radix_build_index (trie index maps, including its one 8-byte device-to-host read of N')
+followed by radix_prefill_forward (compact-space position-wise ops + full-layout attention).
+The headline value is uncompressed tokens per second, N / step time.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
+
+WORKLOAD_TEXT = {
+    "C1": "C1: tiny Qwen3-style decoder fp32, 8 seqs = 32 shared + 16 own tokens",
+    "C2": "C2: Qwen3-0.6B shape, reranking batch of 64 seqs = 48-token shared prefix + suffix U[64,192]",
+    "C3": "C3: Qwen3-4B shape, 128 seqs = 256 shared + 8 query groups x 32 + suffix U[64,192]",
+    "C4": "C4: Qwen3-8B shape, reranking batch of 256 seqs = 64 shared + suffix U[96,256]",
+    "C5": "C5: Qwen3-0.6B shape, 128 seqs = 2048-token shared prefix + 32 own tokens",
+    "C5ctl": "C5 control: Qwen3-0.6B shape, 128 x 2080 tokens, no sharing, dedup forced on",
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough budget of the oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2601_15013_amd import binding, harness, synth
+
+    binding.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    key = args.workload
+    batch = synth.make_batch(key)
+    weights = synth.make_weights(key)
+    cfg = weights.cfg
+    model = harness.upload_model(weights)
+    run = harness.Runner(model, batch.N, batch.B)
+    tok, cu = harness.upload_batch(batch)
+    N, B, max_len = batch.N, batch.B, batch.max_seqlen
+    out = torch.empty((N, cfg.d), dtype=torch.float32, device="cuda")
+    I_s = torch.empty(N, dtype=torch.int32, device="cuda")
+    I_g = torch.empty(N, dtype=torch.int32, device="cuda")
+    n_dev = torch.empty(1, dtype=torch.int32, device="cuda")
+    force = key == "C5ctl"
+
+    def step():
+        maps = binding.radix_build_index(tok, None, cu, run.ws, I_s, I_g, n_dev)
+        binding.radix_prefill_forward(model, tok, None, cu, max_len, maps[0], maps[1], maps[3], run.ws, out=out,
+                                      force_dedup=force)
+        return maps[3]
+
+    def timed(fn, iters):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / iters
+
+    # ---- headline: W warm-up steps, then exactly K timed steps; the dominant kernel (gate/up
+    # GEMM + SwiGLU) is bracketed by HIP events on the launch stream inside the timed region
+    for _ in range(args.warmup):
+        n_c = step()
+    dominant = "gemm_gateup"
+    binding.radix_timing_enable([dominant])
+    ms_per_step = timed(step, args.steps)
+    t_dom, n_dom = binding.radix_timing_collect()[dominant]
+    binding.radix_timing_enable([])
+    assert run.status() == 0
+    n_c = int(n_dev.item())
+
+    # ---- context numbers (outside the timed region)
+    maps = (I_s, I_g, n_dev, n_c)
+    k2 = max(3, min(args.steps, 10))
+    t_build = timed(lambda: binding.radix_build_index(tok, None, cu, run.ws, I_s, I_g, n_dev), k2)
+    t_fwd = timed(lambda: binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out,
+                                                        force_dedup=force), k2)
+    t_nodedup = timed(lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, max_len, run.ws, out=out), k2)
+    binding.radix_timing_enable(binding.TIMING_CATEGORIES)
+    binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out, force_dedup=force)
+    per_kernel = binding.radix_timing_collect()
+    binding.radix_timing_enable([])
+
+    d, di, dq, dkv = cfg.d, cfg.d_int, cfg.dq, cfg.dkv
+    flops_dom = 2.0 * n_c * (2 * di) * d                      # one gate/up GEMM launch
+    avg_dom_s = t_dom / max(n_dom, 1) * 1e-3
+    achieved = flops_dom / avg_dom_s / 1e12
+    peak = PEAK_TFLOPS[cfg.dtype]
+    gemm_flops_layer = n_c * (2.0 * d * (dq + 2 * dkv) + 2.0 * dq * d + 6.0 * d * di)
+    gemm_ms = sum(per_kernel[k][0] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down"))
+    lens = np.diff(batch.cu_seqlens).astype(np.float64)
+    attn_flops = float(np.sum(2.0 * cfg.n_q_heads * cfg.head_dim * (lens * lens + lens))) * cfg.n_layers
+    es = 2 if cfg.dtype != "f32" else 4
+    scatter_bytes = (n_c + N) * (dq + 2 * dkv) * es
+    gather_bytes = 2 * n_c * dq * es
+
+    result = {
+        "metric": "prefill tokens/s (uncompressed)",
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[key], "B": B, "N": N, "N_compact": n_c,
+                   "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": synth.WORKLOADS[key].seed},
+        "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
+        "speedup_vs_nodedup": t_nodedup / t_fwd,
+        "speedup_vs_nodedup_incl_build": t_nodedup / (t_fwd + t_build),
+        "nodedup_tokens_per_s": N / (t_nodedup * 1e-3),
+        "kernel_ms_per_forward": {k: v[0] for k, v in per_kernel.items()},
+        "compact_gemm_tflops": gemm_flops_layer * cfg.n_layers / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
+        "compact_gemm_frac_of_peak": (gemm_flops_layer * cfg.n_layers / (gemm_ms * 1e-3) / 1e12 / peak) if gemm_ms > 0 else None,
+        "attention_tflops": attn_flops / (per_kernel["attention"][0] * 1e-3) / 1e12 if per_kernel["attention"][0] > 0 else None,
+        "scatter_GBps": scatter_bytes * cfg.n_layers / (per_kernel["scatter"][0] * 1e-3) / 1e9 if per_kernel["scatter"][0] > 0 else None,
+        "gather_GBps": gather_bytes * cfg.n_layers / (per_kernel["gather"][0] * 1e-3) / 1e9 if per_kernel["gather"][0] > 0 else None,
+        "roofline": {"kernel": "gate/up GEMM + SwiGLU (M=N', N=2*d_int, K=d)", "bound": "mfma", "achieved": achieved,
+                     "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(batch, weights, args.cpu_seconds)
+
+    model.close()
+    print(json.dumps(result))
+    return 0
+
+
+def cpu_baseline(batch, weights, budget_s):
+    """The oracle as it stands (fp64, no deduplication), timed on the host cores on a bounded sample
+    of whole sequences of the same batch."""
+    import torch
+    from oracle import forward as oracle_forward
+    cfg = weights.cfg
+    embed, gf = weights.embed, weights.gf
+    layers = [weights.layer(l) for l in range(cfg.n_layers)]      # generated before the clock starts
+    seqs, tokens = [], 0
+    t_used, rate = 0.0, None
+    # time one sequence first, then as many more as the budget allows
+    order = list(range(batch.B))
+    i = 0
+    total_t, total_tok = 0.0, 0
+    chunk = 1
+    while i < len(order) and total_t < budget_s:
+        take = order[i:i + chunk]
+        i += len(take)
+        t0 = time.perf_counter()
+        oracle_forward.forward_nodedup(cfg, embed, layers, gf, batch.tok, batch.cu_seqlens, sequences=take)
+        dt = time.perf_counter() - t0
+        total_t += dt
+        total_tok += int(sum(batch.cu_seqlens[s + 1] - batch.cu_seqlens[s] for s in take))
+        seqs += take
+        if total_t > 0:
+            per_seq = total_t / len(seqs)
+            chunk = max(1, min(8, int((budget_s - total_t) / max(per_seq, 1e-3) / 2)))
+    return {"value": total_tok / total_t, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"fp64 no-dedup oracle on the first {len(seqs)} whole sequences ({total_tok} tokens) of the same "
+                      f"batch, all {cfg.n_layers} layers, {total_t:.1f} s"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -185,6 +185,28 @@ int radix_index_select_rows(const void* src, int32_t n_src_rows, const int32_t* 
  * clearing the status word; RADIX_OK if nothing was recorded). */
 int radix_device_status(void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Optional per-kernel timing for benchmarks.  While a category's bit is set in category_mask,
+ * the forward calls bracket every launch of that category with a pair of HIP events recorded on
+ * the caller's stream.  radix_timing_collect waits for the device, writes for every category the
+ * summed elapsed milliseconds and the number of timed launches since the last collect/enable
+ * (arrays of RADIX_TIMING_CATEGORIES entries, HOST pointers) and resets the counters.
+ * Process-wide state, not thread-safe; meant for one benchmarking thread.  Mask 0 disables.
+ */
+enum {
+    RADIX_TIME_GEMM_QKV = 0,
+    RADIX_TIME_GEMM_O = 1,
+    RADIX_TIME_GEMM_GATEUP = 2,
+    RADIX_TIME_GEMM_DOWN = 3,
+    RADIX_TIME_ATTENTION = 4,
+    RADIX_TIME_SCATTER = 5,
+    RADIX_TIME_GATHER = 6,
+    RADIX_TIME_ROWOPS = 7,
+    RADIX_TIMING_CATEGORIES = 8
+};
+int radix_timing_enable(uint32_t category_mask);
+int radix_timing_collect(float* total_ms_host, int32_t* launches_host);
+
 /* Static description of a radix_status value. */
 const char* radix_status_string(int status);
 

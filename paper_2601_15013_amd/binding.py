@@ -21,7 +21,10 @@ EXPORTS = (
     "radix_model_create", "radix_model_destroy", "radix_index_workspace_bytes", "radix_workspace_bytes",
     "radix_build_index", "radix_prefill_forward", "radix_prefill_forward_nodedup",
     "radix_index_select_rows", "radix_device_status", "radix_status_string",
+    "radix_timing_enable", "radix_timing_collect",
 )
+
+TIMING_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "attention", "scatter", "gather", "rowops")
 
 
 class RadixError(RuntimeError):
@@ -70,6 +73,8 @@ def _lib() -> C.CDLL:
         lib.radix_prefill_forward_nodedup.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
         lib.radix_index_select_rows.argtypes = [vp, i32, vp, i32, sz, vp, vp, vp]
         lib.radix_device_status.argtypes = [vp, sz, vp]
+        lib.radix_timing_enable.argtypes = [C.c_uint32]
+        lib.radix_timing_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
         lib.radix_status_string.argtypes = [C.c_int]
         lib.radix_status_string.restype = C.c_char_p
         for n in EXPORTS:
@@ -228,6 +233,22 @@ def radix_index_select_rows(src: torch.Tensor, idx: torch.Tensor, out: Optional[
 
 def radix_device_status(ws: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> int:
     return _lib().radix_device_status(_ptr(ws), ws.numel(), _stream(stream))
+
+
+def radix_timing_enable(categories: Sequence[str]) -> None:
+    mask = 0
+    for c in categories:
+        mask |= 1 << TIMING_CATEGORIES.index(c)
+    _check(_lib().radix_timing_enable(mask), "radix_timing_enable")
+
+
+def radix_timing_collect() -> dict:
+    """{category: (total_ms, launches)} since the last collect."""
+    n = len(TIMING_CATEGORIES)
+    ms = (C.c_float * n)()
+    cnt = (C.c_int32 * n)()
+    _check(_lib().radix_timing_collect(ms, cnt), "radix_timing_collect")
+    return {TIMING_CATEGORIES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
 def radix_status_string(code: int) -> str:

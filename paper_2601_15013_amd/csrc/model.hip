@@ -27,6 +27,37 @@ struct radix_model {
 
 namespace {
 
+// ---- optional per-kernel timing with HIP events on the caller's stream (used by the benchmark
+// to measure a kernel's average launch duration inside the timed region)
+struct KernelTimer {
+    uint32_t mask = 0;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool[RADIX_TIMING_CATEGORIES];
+    size_t used[RADIX_TIMING_CATEGORIES] = {};
+    int begin(int cat, hipStream_t s) {
+        if (!(mask >> cat & 1u)) return -1;
+        if (used[cat] == pool[cat].size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1;
+            pool[cat].push_back({a, b});
+        }
+        (void)hipEventRecord(pool[cat][used[cat]].first, s);
+        return (int)used[cat];
+    }
+    void end(int cat, int slot, hipStream_t s) {
+        if (slot < 0) return;
+        (void)hipEventRecord(pool[cat][slot].second, s);
+        used[cat] = (size_t)slot + 1;
+    }
+};
+KernelTimer g_timer;
+
+struct TimedScope {
+    int cat, slot;
+    hipStream_t s;
+    TimedScope(int c, hipStream_t st) : cat(c), slot(g_timer.begin(c, st)), s(st) {}
+    ~TimedScope() { g_timer.end(cat, slot, s); }
+};
+
 __global__ void interleave_gate_up_kernel(const uint4* __restrict__ wg, const uint4* __restrict__ wu, int d_int,
                                           int row_vecs, uint4* __restrict__ dst) {
     const int R = blockIdx.x;                  // destination row in [0, 2 d_int)
@@ -247,26 +278,54 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     int rc = RADIX_OK;
     for (int l = 0; l < c.n_layers; ++l) {
         const radix_layer_dev& Lw = model->layers[l];
-        launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
-        if ((rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv)) != RADIX_OK) return rc;
-        launch_qknorm_rope(qkv, dt, M, c.n_q_heads, c.n_kv_heads, hd, c.qk_norm, Lw.gq, Lw.gk, c.eps, pos_c,
-                           model->cos_tab, model->sin_tab, stream);
-        if (dedup)   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
-            launch_index_select_rows(qkv, M, Is, N, (size_t)row * es, qkv_full, hdr, stream);
-        if (dt == RADIX_BF16) {
-            rc = launch_attention_bf16((const bf16_t*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,
-                                       (bf16_t*)attn_full, stream);
-            if (rc != RADIX_OK) return rc;
-        } else {
-            launch_attention_f32((const float*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,
-                                 (float*)attn_full, stream);
+        {
+            TimedScope t(RADIX_TIME_ROWOPS, stream);
+            launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
         }
-        if (dedup)   // Gather(a)
+        {
+            TimedScope t(RADIX_TIME_GEMM_QKV, stream);
+            if ((rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv)) != RADIX_OK) return rc;
+        }
+        {
+            TimedScope t(RADIX_TIME_ROWOPS, stream);
+            launch_qknorm_rope(qkv, dt, M, c.n_q_heads, c.n_kv_heads, hd, c.qk_norm, Lw.gq, Lw.gk, c.eps, pos_c,
+                               model->cos_tab, model->sin_tab, stream);
+        }
+        if (dedup) {   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
+            TimedScope t(RADIX_TIME_SCATTER, stream);
+            launch_index_select_rows(qkv, M, Is, N, (size_t)row * es, qkv_full, hdr, stream);
+        }
+        {
+            TimedScope t(RADIX_TIME_ATTENTION, stream);
+            if (dt == RADIX_BF16) {
+                rc = launch_attention_bf16((const bf16_t*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads,
+                                           hd, (bf16_t*)attn_full, stream);
+                if (rc != RADIX_OK) return rc;
+            } else {
+                launch_attention_f32((const float*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,
+                                     (float*)attn_full, stream);
+            }
+        }
+        if (dedup) {   // Gather(a)
+            TimedScope t(RADIX_TIME_GATHER, stream);
             launch_index_select_rows(attn_full, N, Ig, M, (size_t)dq * es, attn_c, hdr, stream);
-        if ((rc = gemm(attn_c, Lw.wo, d, dq, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
-        launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
-        if ((rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp)) != RADIX_OK) return rc;
-        if ((rc = gemm(mlp, Lw.wd, d, c.d_int, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+        }
+        {
+            TimedScope t(RADIX_TIME_GEMM_O, stream);
+            if ((rc = gemm(attn_c, Lw.wo, d, dq, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+        }
+        {
+            TimedScope t(RADIX_TIME_ROWOPS, stream);
+            launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
+        }
+        {
+            TimedScope t(RADIX_TIME_GEMM_GATEUP, stream);
+            if ((rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp)) != RADIX_OK) return rc;
+        }
+        {
+            TimedScope t(RADIX_TIME_GEMM_DOWN, stream);
+            if ((rc = gemm(mlp, Lw.wd, d, c.d_int, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+        }
     }
     if (dedup) {
         launch_rmsnorm(h, model->gf, M, d, c.eps, ynorm, RADIX_F32, stream);
@@ -314,6 +373,29 @@ extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int
     if (rc != RADIX_OK) return rc;
     return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, out, ws, ws_bytes,
                         (hipStream_t)stream);
+}
+
+extern "C" int radix_timing_enable(uint32_t category_mask) {
+    g_timer.mask = category_mask & ((1u << RADIX_TIMING_CATEGORIES) - 1u);
+    for (int c = 0; c < RADIX_TIMING_CATEGORIES; ++c) g_timer.used[c] = 0;
+    return RADIX_OK;
+}
+
+extern "C" int radix_timing_collect(float* total_ms, int32_t* launches) {
+    if (!total_ms || !launches) return RADIX_ERR_NULL_POINTER;
+    HIP_TRY(hipDeviceSynchronize());
+    for (int c = 0; c < RADIX_TIMING_CATEGORIES; ++c) {
+        double sum = 0.0;
+        for (size_t i = 0; i < g_timer.used[c]; ++i) {
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, g_timer.pool[c][i].first, g_timer.pool[c][i].second));
+            sum += ms;
+        }
+        total_ms[c] = (float)sum;
+        launches[c] = (int32_t)g_timer.used[c];
+        g_timer.used[c] = 0;
+    }
+    return RADIX_OK;
 }
 
 extern "C" const char* radix_status_string(int status) {
