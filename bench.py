@@ -110,7 +110,7 @@ def main() -> int:
     flops_dom = 2.0 * n_c * (2 * di) * d                      # one gate/up GEMM launch
     avg_dom_s = t_dom / max(n_dom, 1) * 1e-3
     achieved = flops_dom / avg_dom_s / 1e12
-    peak = PEAK_TFLOPS[cfg.dtype]
+    peak = PEAK_TFLOPS[cfg.compute_dtype]
     gemm_flops_layer = n_c * (2.0 * d * (dq + 2 * dkv) + 2.0 * dq * d + 6.0 * d * di)
     gemm_ms = sum(per_kernel[k][0] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down"))
     lens = np.diff(batch.cu_seqlens).astype(np.float64)
@@ -130,10 +130,11 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": cfg.dtype,
+        "dtype": cfg.compute_dtype,
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[key], "B": B, "N": N, "N_compact": n_c,
-                   "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": synth.WORKLOADS[key].seed},
+                   "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": synth.WORKLOADS[key].seed,
+                   "weights": cfg.dtype, "operands": cfg.compute_dtype, "accumulate": "f32"},
         "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
         "speedup_vs_nodedup": t_nodedup / t_fwd,
         "speedup_vs_nodedup_incl_build": t_nodedup / (t_fwd + t_build),

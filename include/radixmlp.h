@@ -45,7 +45,7 @@ typedef enum radix_status {
     RADIX_ERR_BAD_CONFIG = -9         /* inconsistent model configuration */
 } radix_status;
 
-typedef enum radix_dtype { RADIX_F32 = 0, RADIX_BF16 = 1 } radix_dtype;
+typedef enum radix_dtype { RADIX_F32 = 0, RADIX_BF16 = 1, RADIX_F16 = 2 } radix_dtype;
 
 /* Shape of the decoder (paper: Background, Eqs. 1-2 and Eq. 5). */
 typedef struct radix_model_config {
@@ -58,7 +58,12 @@ typedef struct radix_model_config {
     int32_t vocab;
     int32_t max_pos;     /* RoPE table length; position ids must be < max_pos */
     int32_t qk_norm;     /* 1: per-head RMSNorm of q and k before RoPE (Qwen3) */
-    int32_t dtype;       /* radix_dtype: storage type of matrices and of GEMM operands */
+    int32_t dtype;       /* radix_dtype of the weights handed to radix_model_create: RADIX_F32 or RADIX_BF16 */
+    int32_t compute_dtype; /* radix_dtype of activations and MFMA operands (accumulation is always fp32):
+                              RADIX_F32 with fp32 weights; RADIX_BF16 or RADIX_F16 with bf16 weights.
+                              RADIX_F16 converts the weights once at create time (exact for every bf16
+                              value of magnitude >= 2^-17) and carries 11-bit instead of 8-bit
+                              significands through the activations; activations must stay below 65504. */
     float eps;           /* RMSNorm epsilon (inside the square root) */
     float rope_base;
 } radix_model_config;
@@ -96,7 +101,7 @@ typedef struct radix_fwd_opts {
 
 /*
  * radix_model_create - validate the configuration, build library-owned device copies of the
- * weights in the layouts the kernels use (fused QKV matrix, gate/up interleaved) and the fp32
+ * weights in the layouts the kernels use (fused QKV matrix, gate/up interleaved, operand type) and the fp32
  * RoPE cos/sin tables (angle p * base^(-2i/hd) evaluated in double precision; element i is
  * paired with i + hd/2).  Synchronous.  The caller keeps ownership of the source weights and may
  * free them once the call returns.  On error *out is NULL.

@@ -12,8 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libradixmlp.so")
 
-SOURCES = ["index_build.hip", "rowops.hip", "gemm_f32.hip", "gemm_bf16.hip", "attention_f32.hip",
-           "attention_bf16.hip", "model.hip"]
+SOURCES = ["index_build.hip", "rowops.hip", "gemm_f32.hip", "gemm_mfma.hip", "attention_f32.hip",
+           "attention_mfma.hip", "model.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,10 +1,10 @@
-// bf16 causal varlen GQA attention on the full ragged layout (head_dim = 128), MFMA + online
+// 16-bit (bf16 or fp16 operands) causal varlen GQA attention on the full ragged layout (head_dim = 128), MFMA + online
 // softmax.  (Paper: Algorithm 1, "FlashAttn(q, k, v, cu_seqlens, causal=True)"; "Integration
 // with Attention": attention is the only step that needs all N rows.)
 //
 // One workgroup = 128 query rows of one (sequence, query head); 4 wavefronts x 32 queries.
 // Keys/values are walked in tiles of 64 staged in LDS.  Scores are produced TRANSPOSED,
-// S^T[key, query] = K * Q^T with v_mfma_f32_32x32x16_bf16, so that a lane owns one query column:
+// S^T[key, query] = K * Q^T with v_mfma_f32_32x32x16_{bf16,f16}, so that a lane owns one query column:
 // row maxima and sums are in-lane reductions plus one exchange with lane ^ 32, and the running
 // rescale factor is a per-lane scalar.  The second product is O^T[hd, query] = V^T * P^T, whose
 // B operand is exactly the register layout S^T was produced in (the k index of an MFMA may be
@@ -20,12 +20,16 @@ constexpr int BQ = 128;     // queries per workgroup
 constexpr int BKV = 64;     // keys per tile
 constexpr int ATT_THREADS = 256;
 
-__global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_t* __restrict__ qkv,
+template <int DT>
+__global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
                                                                      const int32_t* __restrict__ cu, int N,
                                                                      int n_q_heads, int n_kv_heads, int n_qtiles,
-                                                                     bf16_t* __restrict__ out) {
+                                                                     typename Op<DT>::T* __restrict__ out) {
+    typedef typename Op<DT>::T T;
+    typedef typename Op<DT>::V8 V8;
+    typedef typename Op<DT>::V4 V4;
     __shared__ uint4 Ks[BKV * 16];          // [key][16 chunks of 8 hd], chunk ^= key & 15
-    __shared__ uint32_t Vt[HD * 32];        // [hd][32 words of 2 keys], 8-byte chunk ^= hd & 15
+    __shared__ uint32_t Vt[HD * 32];        // [hd][32 words of 2 keys], 8-byte chunk ^= (hd >> 1) & 15
 
     const int seq = blockIdx.z, h = blockIdx.y;
     const int qt = n_qtiles - 1 - (int)blockIdx.x;      // heavy (late) tiles first
@@ -43,19 +47,19 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_
     const int kvh = h / group;
     const int dq = n_q_heads * HD, dkv = n_kv_heads * HD;
     const size_t row = (size_t)dq + 2 * (size_t)dkv;
-    const bf16_t* kbase = qkv + (size_t)start * row + dq + (size_t)kvh * HD;
-    const bf16_t* vbase = kbase + dkv;
+    const T* kbase = qkv + (size_t)start * row + dq + (size_t)kvh * HD;
+    const T* vbase = kbase + dkv;
 
     // ---- Q fragment (B operand of S^T = K Q^T): lane (n, g) holds Q[query n][16 ks + 8 g .. +8]
     const int qi = q0 + wave * 32 + n;                  // query offset inside the sequence
     const int qi_c = qi < len ? qi : len - 1;
-    bf16x8 qf[8];
+    V8 qf[8];
     {
         const uint4* qp = (const uint4*)(qkv + (size_t)(start + qi_c) * row + (size_t)h * HD);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 v = qp[ks * 2 + g];
-            qf[ks] = *reinterpret_cast<bf16x8*>(&v);
+            qf[ks] = *reinterpret_cast<V8*>(&v);
         }
     }
 
@@ -99,7 +103,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_
                     const uint32_t lo = (aw[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
                     const uint32_t hi = (bw[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
                     const int hd = c8 * 8 + e;
-                    Vt[hd * 32 + (((n >> 1) ^ (hd & 15)) << 1) + (n & 1)] = lo | (hi << 16);
+                    Vt[hd * 32 + (((n >> 1) ^ ((hd >> 1) & 15)) << 1) + (n & 1)] = lo | (hi << 16);
                 }
             }
         }
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 uint4 v = Ks[key * 16 + ((ks * 2 + g) ^ (key & 15))];
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&v), qf[ks], s[kb], 0, 0, 0);
+                s[kb] = Op<DT>::mfma(*reinterpret_cast<V8*>(&v), qf[ks], s[kb]);
             }
         }
         // ---- scale, causal mask (register e of block kb is key kv0 + 32 kb + 8 (e/4) + 4 g + e%4)
@@ -139,14 +143,14 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_
         const float alpha = exp2f(m_run - m_new);
         m_run = m_new;
         float psum = 0.f;
-        bf16x8 pf[4];
+        V8 pf[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float p = exp2f(s[kb][e] - m_new);
                 psum += p;
-                pf[kb * 2 + (e >> 3)][e & 7] = (bf16_t)p;
+                pf[kb * 2 + (e >> 3)][e & 7] = (T)p;
             }
         l_run = l_run * alpha + psum;
 #pragma unroll
@@ -160,10 +164,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 const int hd = b * 32 + n;
-                const uint2 lo = *reinterpret_cast<const uint2*>(&Vt[hd * 32 + (((4 * kk + g) ^ (hd & 15)) << 1)]);
-                const uint2 hi = *reinterpret_cast<const uint2*>(&Vt[hd * 32 + (((4 * kk + 2 + g) ^ (hd & 15)) << 1)]);
+                const uint2 lo = *reinterpret_cast<const uint2*>(&Vt[hd * 32 + (((4 * kk + g) ^ ((hd >> 1) & 15)) << 1)]);
+                const uint2 hi = *reinterpret_cast<const uint2*>(&Vt[hd * 32 + (((4 * kk + 2 + g) ^ ((hd >> 1) & 15)) << 1)]);
                 uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&v), pf[kk], o[b], 0, 0, 0);
+                o[b] = Op<DT>::mfma(*reinterpret_cast<V8*>(&v), pf[kk], o[b]);
             }
         }
     }
@@ -172,29 +176,36 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_bf16_kernel(const bf16_
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (qi < len) {
         const float inv = 1.0f / l_tot;
-        bf16_t* op = out + (size_t)(start + qi) * dq + (size_t)h * HD;
+        T* op = out + (size_t)(start + qi) * dq + (size_t)h * HD;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                bf16x4 v;
+                V4 v;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) v[j] = (bf16_t)(o[b][q4 * 4 + j] * inv);
-                *reinterpret_cast<bf16x4*>(op + b * 32 + q4 * 8 + g * 4) = v;
+                for (int j = 0; j < 4; ++j) v[j] = (T)(o[b][q4 * 4 + j] * inv);
+                *reinterpret_cast<V4*>(op + b * 32 + q4 * 8 + g * 4) = v;
             }
     }
 }
 
 }  // namespace
 
-int launch_attention_bf16(const bf16_t* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, bf16_t* out, hipStream_t stream) {
+int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream) {
     if (N <= 0 || B <= 0) return RADIX_OK;
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
     if (max_seqlen <= 0) return RADIX_ERR_BAD_SIZE;
     if (B > 65535 || n_q_heads > 65535) return RADIX_ERR_UNSUPPORTED;
     const int n_qtiles = ceil_div(max_seqlen, BQ);
-    hipLaunchKernelGGL(attention_bf16_kernel, dim3(n_qtiles, n_q_heads, B), dim3(ATT_THREADS), 0, stream, qkv, cu,
-                       N, n_q_heads, n_kv_heads, n_qtiles, out);
+    const dim3 grid(n_qtiles, n_q_heads, B), block(ATT_THREADS);
+    if (op_dtype == RADIX_BF16)
+        hipLaunchKernelGGL(attention_mfma_kernel<RADIX_BF16>, grid, block, 0, stream, (const bf16_t*)qkv, cu, N,
+                           n_q_heads, n_kv_heads, n_qtiles, (bf16_t*)out);
+    else if (op_dtype == RADIX_F16)
+        hipLaunchKernelGGL(attention_mfma_kernel<RADIX_F16>, grid, block, 0, stream, (const f16_t*)qkv, cu, N,
+                           n_q_heads, n_kv_heads, n_qtiles, (f16_t*)out);
+    else
+        return RADIX_ERR_UNSUPPORTED;
     return RADIX_OK;
 }

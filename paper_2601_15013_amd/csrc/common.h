@@ -9,6 +9,9 @@ typedef __bf16 bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef _Float16 f16_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -37,9 +40,32 @@ __device__ __forceinline__ float wave_max(float v) {
 template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+template <> __device__ __forceinline__ float to_f32<f16_t>(f16_t v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ f16_t from_f32<f16_t>(float v) { return (f16_t)v; }
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+// 16-bit MFMA operand types: v_mfma_f32_32x32x16_{bf16,f16}.  Lane (r = lane % 32, g = lane / 32)
+// supplies 8 consecutive k of row r (k-group g) for both operands; accumulator register e of the
+// 32x32 result is row 8 (e / 4) + 4 g + e % 4, column r.
+template <int DT> struct Op;
+template <> struct Op<RADIX_BF16> {
+    typedef bf16_t T;
+    typedef bf16x8 V8;
+    typedef bf16x4 V4;
+    static __device__ __forceinline__ f32x16 mfma(V8 a, V8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Op<RADIX_F16> {
+    typedef f16_t T;
+    typedef f16x8 V8;
+    typedef f16x4 V4;
+    static __device__ __forceinline__ f32x16 mfma(V8 a, V8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
 
 // Device status word: first error wins.
 __device__ __forceinline__ void set_status(int32_t* status, int32_t code) {

@@ -1,0 +1,356 @@
+// 16-bit MFMA GEMM  C[M, Nout] = A[M, K] * W[Nout, K]^T  (fp32 accumulate) with fused epilogues,
+// for bf16 or fp16 operands.
+//
+// These are the position-wise contractions of the method - Q/K/V and O projections and the
+// SwiGLU MLP (paper: Background Eq. 5; Algorithm 1 "QKVProj", "OProj", "MLP") - run on the
+// compact row count M = N' (or M = N in the no-dedup baseline).  Both operands are K-contiguous
+// ("NT" GEMM), which is exactly the per-lane operand layout of v_mfma_f32_32x32x16_{bf16,f16}:
+// lane (r = lane % 32, g = lane / 32) supplies 8 consecutive k of row r for k-group g.
+//
+// Structure
+//   * Workgroup tile BM x BN, k-tile 32, 256 threads = 4 wavefronts in a WAVES_M x WAVES_N grid;
+//     each wavefront owns (BM/WAVES_M) x (BN/WAVES_N) outputs as 32x32 MFMA accumulators.
+//   * The product is formed transposed, C^T = W * A^T (weights are the MFMA "A" operand), so a
+//     lane owns one output ROW and 4 consecutive columns per register quad: epilogue stores are
+//     8 bytes (16-bit out) or 16 bytes (fp32 residual read-modify-write) per lane.
+//   * Global -> LDS goes through global_load_lds_dwordx4 (no VGPR staging): a wavefront fills
+//     1 KB of LDS per instruction, lane L landing at byte 16 L; the XOR swizzle that keeps the
+//     fragment reads bank-conflict free is therefore applied to the GLOBAL address each lane
+//     fetches.  Four LDS stages, one barrier per k-tile, loads issued three tiles ahead.  The
+//     load is issued from inline assembly: issued through the compiler builtin, the compiler's
+//     wait-count pass makes every later LDS read wait for ALL loads in flight (it cannot prove
+//     that the reads of one stage do not alias the fills of the others), which serialises the
+//     pipeline.  The only vector-memory waits are the explicit ones in front of the barriers.
+//   * K is consumed in order and there is no split-K, so an output element is reduced in the
+//     same order wherever its row sits in the matrix: the deduplicated and the no-dedup pass
+//     give bit-identical rows.
+//   * Ragged M: rows >= M are fetched from row M-1 and never stored.
+//   * Workgroups are numbered so that the 8 XCDs (round-robin dispatch) each work on a compact
+//     band of row tiles, sweeping the weight tiles, which keeps an XCD's L2 on few A rows.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+constexpr int BK = 32;            // k-tile: 64 bytes = 4 chunks of 16 bytes per row
+constexpr int GEMM_THREADS = 256;
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt = imm[15:14|3:0],
+// expcnt = imm[6:4], lgkmcnt = imm[11:8]).
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Asynchronous 16-byte-per-lane copy global -> LDS: lane L of the wavefront writes LDS bytes
+// [lds_base + 16 L, +16).  lds_base must be wave-uniform.  (s_nop: M0 write -> LDS-DMA hazard.)
+// The global address is (uniform 64-bit base) + (per-lane 32-bit byte offset).
+__device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+// LDS slot (in 16-byte units) of chunk c of tile row `row`.  Rows are 4 chunks (64 bytes), so rows
+// r, r+4, r+8, r+12 start in the same 64-byte window of the 256-byte bank line; XORing the chunk
+// index with bits 2..3 of the row sends the 16 lanes that a ds_read_b128 serves per cycle (16
+// consecutive rows of one chunk column) to 16 distinct 16-byte bank groups.
+__device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int slot(int row, int c) { return row * 4 + (c ^ swz(row)); }
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename Op<DT>::T* __restrict__ A,
+                                                                 const typename Op<DT>::T* __restrict__ W, int M,
+                                                                 int Nout, int K, void* __restrict__ out_,
+                                                                 int tiles_m, int tiles_n) {
+    typedef typename Op<DT>::T T;
+    typedef typename Op<DT>::V8 V8;
+    typedef typename Op<DT>::V4 V4;
+    static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts");
+    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    constexpr int MB = WTM / 32, NB = WTN / 32;
+    constexpr int A_LOADS = BM / 64, B_LOADS = BN / 64;        // 1 KB wave-loads per wavefront per k-tile
+    constexpr int LOADS = A_LOADS + B_LOADS;
+    constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
+    static_assert(EPI != EPI_SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
+    static_assert(LOADS * 3 < 64, "vmcnt range");
+
+    constexpr int EPI_PITCH = 272;                             // epilogue row pitch in bytes (256 + 16 pad)
+    constexpr int EPI_SLOTS = 4 * 64 * EPI_PITCH / 16;         // 4 wavefronts x 64 rows
+    constexpr int LDS_SLOTS = 4 * STAGE > EPI_SLOTS ? 4 * STAGE : EPI_SLOTS;
+    __shared__ uint4 lds_all[LDS_SLOTS];
+    uint4* const st0 = lds_all;
+    uint4* const st1 = lds_all + STAGE;
+    uint4* const st2 = lds_all + 2 * STAGE;
+    uint4* const st3 = lds_all + 3 * STAGE;
+
+    // ---- tile assignment: XCD-aware renumbering, then row-tile bands of 8 sweeping the columns
+    int pid = blockIdx.x;
+    {
+        const int nblk = tiles_m * tiles_n;
+        const int per = nblk / 8, rem = nblk % 8;       // XCD x gets `per` (+1 if x < rem) blocks
+        const int x = pid % 8, q = pid / 8;
+        pid = x * per + (x < rem ? x : rem) + q;
+    }
+    constexpr int BAND = 8;
+    const int band = pid / (BAND * tiles_n);
+    const int band_rows = (tiles_m - band * BAND) < BAND ? (tiles_m - band * BAND) : BAND;
+    const int in_band = pid - band * BAND * tiles_n;
+    const int tm = band * BAND + in_band % band_rows;
+    const int tn = in_band / band_rows;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int r = lane & 31, g = lane >> 5;
+
+    // ---- global-load assignment.  Wave-load j of this wavefront fills tile rows
+    // [16 (wave + 4 j), +16): lane L -> row + L / 4, LDS chunk L % 4, global chunk (L % 4) ^ swz(row).
+    // Addresses are (uniform 64-bit tile base, advanced per k-tile) + (per-lane 32-bit byte offset).
+    const int lrow = lane >> 2, lpc = lane & 3;
+    const int m_last = M - 1 - m0;                              // last valid row of this tile (ragged M)
+    uint32_t a_off[A_LOADS], w_off[B_LOADS];
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) {
+        const int row = 16 * (wave + 4 * j) + lrow;
+        const int src = row < m_last ? row : m_last;
+        a_off[j] = (uint32_t)(((size_t)src * K + 8 * (lpc ^ swz(row))) * sizeof(T));
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) {
+        const int row = 16 * (wave + 4 * j) + lrow;
+        w_off[j] = (uint32_t)(((size_t)row * K + 8 * (lpc ^ swz(row))) * sizeof(T));
+    }
+    const char* a_base = (const char*)(A + (size_t)m0 * K);
+    const char* w_base = (const char*)(W + (size_t)n0 * K);
+
+    f32x16 acc[NB][MB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+    const int KT = K / BK;
+
+    // fragment f of a k-step: f < MB is an activation fragment, else a weight fragment
+#define RADIX_FRAG1(ST, KS, FA, FB, F)                                                                             \
+    do {                                                                                                           \
+        const int ch = (KS) * 2 + g;                                                                               \
+        if ((F) < MB) {                                                                                            \
+            uint4 v = (ST)[slot(wm * WTM + (F) * 32 + r, ch)];                                                     \
+            FA[(F) < MB ? (F) : 0] = *reinterpret_cast<V8*>(&v);                                                   \
+        } else {                                                                                                   \
+            uint4 v = (ST)[BM * 4 + slot(wn * WTN + ((F) - MB) * 32 + r, ch)];                                     \
+            FB[(F) >= MB ? (F) - MB : 0] = *reinterpret_cast<V8*>(&v);                                             \
+        }                                                                                                          \
+    } while (0)
+
+#define RADIX_DMA1(KB, ST, F)                                                                                      \
+    do {                                                                                                           \
+        if ((F) < A_LOADS)                                                                                         \
+            dma16(a_base + (KB), a_off[(F) < A_LOADS ? (F) : 0], lds_addr((ST) + 64 * (wave + 4 * (F))));          \
+        else if ((F) < LOADS)                                                                                      \
+            dma16(w_base + (KB), w_off[(F) >= A_LOADS && (F) < LOADS ? (F) - A_LOADS : 0],                         \
+                  lds_addr((ST) + BM * 4 + 64 * (wave + 4 * ((F) - A_LOADS))));                                    \
+    } while (0)
+
+#define RADIX_ISSUE(TILE, ST)                                                                                      \
+    do {                                                                                                           \
+        const size_t kb_ = (size_t)((TILE) < KT ? (TILE) : KT - 1) * (BK * sizeof(T));                             \
+        _Pragma("unroll") for (int f = 0; f < LOADS; ++f) RADIX_DMA1(kb_, ST, f);                                  \
+    } while (0)
+
+    // MFMAs [lo, hi) of the MB x NB block products of one k-step, in (j, i) order
+#define RADIX_MFMA_RANGE(FA, FB, LO, HI)                                                                           \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int t = (LO); t < (HI); ++t)                                                        \
+            acc[t / MB][t % MB] = Op<DT>::mfma(FB[t / MB], FA[t % MB], acc[t / MB][t % MB]);                       \
+    } while (0)
+
+    // One k-tile = two k-steps of 16, software-pipelined over two fragment register sets and
+    // scheduled by hand (the scheduling barriers pin the order): the first half of a k-step's MFMAs
+    // is cut into UNITS slices, each led by one LDS fragment read for the NEXT k-step (and, in the
+    // second k-step, one global->LDS load of the tile three ahead); the second half of the MFMAs then
+    // covers the LDS latency of those reads, so the matrix pipe always has queued work.
+    // Between the two k-steps of tile kt+O: wait for this wavefront's share of tile kt+O+1, barrier
+    // (everybody's share has landed and everybody is past tile kt+O-1), then refill the stage tile
+    // kt+O-1 occupied with tile kt+O+3.  Tiles past the end are re-fetches of the last tile into a
+    // stage nobody reads again, which keeps the load-counter bookkeeping uniform.
+#define RADIX_STEP(CUR, NXT, REFILL, O)                                                            \
+    if (kt + (O) < KT) {                                                                           \
+        _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                        \
+            RADIX_FRAG1(CUR, 1, fa1, fb1, u);                                                      \
+            RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);                  \
+            __builtin_amdgcn_sched_barrier(0);                                                     \
+        }                                                                                          \
+        RADIX_MFMA_RANGE(fa0, fb0, HALF, MB * NB);                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                         \
+        wait_vmcnt<LOADS>();                                                                       \
+        __builtin_amdgcn_s_barrier();                                                              \
+        {                                                                                          \
+            const size_t kb_ = (size_t)(kt + (O) + 3 < KT ? kt + (O) + 3 : KT - 1) * (BK * sizeof(T)); \
+            _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                    \
+                RADIX_DMA1(kb_, REFILL, u);                                                        \
+                RADIX_FRAG1(NXT, 0, fa0, fb0, u);                                                  \
+                RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);              \
+                __builtin_amdgcn_sched_barrier(0);                                                 \
+            }                                                                                      \
+            RADIX_MFMA_RANGE(fa1, fb1, HALF, MB * NB);                                             \
+            __builtin_amdgcn_sched_barrier(0);                                                     \
+        }                                                                                          \
+    }
+
+    constexpr int UNITS = MB + NB;
+    constexpr int HALF = MB * NB / 2;      // the reads ride on the first half of a k-step's MFMAs
+    static_assert(UNITS >= LOADS, "one global->LDS load per slice");
+    V8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
+    RADIX_ISSUE(0, st0);
+    RADIX_ISSUE(1, st1);
+    RADIX_ISSUE(2, st2);
+    wait_vmcnt<LOADS * 2>();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(st0, 0, fa0, fb0, u);
+    for (int kt = 0; kt < KT; kt += 4) {
+        RADIX_STEP(st0, st1, st3, 0)
+        RADIX_STEP(st1, st2, st0, 1)
+        RADIX_STEP(st2, st3, st1, 2)
+        RADIX_STEP(st3, st0, st2, 3)
+    }
+#undef RADIX_STEP
+#undef RADIX_MFMA_RANGE
+#undef RADIX_ISSUE
+#undef RADIX_DMA1
+#undef RADIX_FRAG1
+    wait_vmcnt<0>();                  // drain the tail loads ...
+    __builtin_amdgcn_s_barrier();     // ... and wait until every wavefront is done with the stages
+
+    // ---- epilogue.  acc[j][i] register e holds output row 32 i + r, column 32 j + 8 (e/4) + 4 g + e%4
+    // of this wavefront's block: a lane owns a ROW.  To write full 128-byte lines the block goes
+    // through LDS in passes of 64 rows: every lane drops its row pieces into a padded row-major
+    // buffer private to its wavefront (row pitch 272 bytes), then the wavefront reads the buffer back
+    // 16 bytes per lane, 16 lanes per 256-byte row, and does the global access from that layout.
+    constexpr int PITCH = EPI_PITCH;
+    char* const ebuf = (char*)lds_all + wave * (64 * PITCH);
+    static_assert(MB % 2 == 0 && NB % 2 == 0, "passes of 64 rows / 64 columns");
+
+    if (EPI == EPI_RESIDUAL) {
+        // fp32 read-modify-write of the residual stream straight from the accumulator layout: per
+        // instruction 32 rows x 32 contiguous bytes; all loads of a row block are issued before its
+        // stores, and nothing has to be converted, so the LDS detour does not pay here.
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int gm = m0 + wm * WTM + i * 32 + r;
+            if (gm >= M) continue;
+            float* orow = (float*)out_ + (size_t)gm * Nout + n0 + wn * WTN;
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4* p = reinterpret_cast<f32x4*>(orow + j * 32 + 8 * q + 4 * g);
+                    f32x4 v = *p;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) v[t] += acc[j][i][q * 4 + t];
+                    *p = v;
+                }
+        }
+    } else {
+        // 16-bit outputs.  EPI_STORE: 128 output columns per wavefront row (256 bytes);
+        // EPI_SWIGLU: gate block j / up block j+1 pairs -> 64 output columns per row (128 bytes).
+        constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? WTN / 2 : WTN;
+        constexpr int CHUNKS = OUT_COLS / 8;                    // 16-byte chunks per output row
+        constexpr int ROWS_PER_INST = 64 / CHUNKS;
+        const int orow = lane / CHUNKS, ochunk = lane % CHUNKS;
+        const int ldo = (EPI == EPI_SWIGLU) ? (Nout >> 1) : Nout;
+        const int ncol0 = (EPI == EPI_SWIGLU) ? ((n0 + wn * WTN) >> 1) : (n0 + wn * WTN);
+#pragma unroll
+        for (int ip = 0; ip < MB; ip += 2) {
+#pragma unroll
+            for (int il = 0; il < 2; ++il) {
+                char* rowp = ebuf + (il * 32 + r) * PITCH;
+                if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                    for (int j = 0; j < NB; j += 2)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            V4 v;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const float gt = acc[j][ip + il][q * 4 + t], up = acc[j + 1][ip + il][q * 4 + t];
+                                v[t] = (T)(gt / (1.0f + __expf(-gt)) * up);
+                            }
+                            *reinterpret_cast<V4*>(rowp + ((j >> 1) * 32 + 8 * q + 4 * g) * 2) = v;
+                        }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            V4 v;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) v[t] = (T)acc[j][ip + il][q * 4 + t];
+                            *reinterpret_cast<V4*>(rowp + (j * 32 + 8 * q + 4 * g) * 2) = v;
+                        }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 64 / ROWS_PER_INST; ++t) {
+                const int row = orow + ROWS_PER_INST * t;
+                const int gm = m0 + wm * WTM + ip * 32 + row;
+                const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * PITCH + ochunk * 16);
+                if (gm < M) *reinterpret_cast<uint4*>((T*)out_ + (size_t)gm * ldo + ncol0 + ochunk * 8) = v;
+            }
+        }
+    }
+}
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
+int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, hipStream_t stream) {
+    typedef typename Op<DT>::T T;
+    if (Nout % BN != 0 || K % BK != 0) return RADIX_ERR_UNSUPPORTED;
+    const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
+    dim3 grid((unsigned)(tiles_m * tiles_n)), block(GEMM_THREADS);
+#define RADIX_LAUNCH(E)                                                                                       \
+    do {                                                                                                      \
+        auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
+        hipLaunchKernelGGL(kfn, grid, block, 0, stream, (const T*)A, (const T*)W, M, Nout, K, out, tiles_m,   \
+                           tiles_n);                                                                          \
+    } while (0)
+    if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
+    else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
+    else RADIX_LAUNCH(EPI_SWIGLU);
+#undef RADIX_LAUNCH
+    return RADIX_OK;
+}
+
+template <int DT>
+int launch_dt(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int variant,
+              hipStream_t stream) {
+    // tile choice: the biggest tile that still gives every CU work
+    const long long t256 = (long long)ceil_div(M, 256) * (Nout / 256);
+    if (variant == 0) {
+        if (Nout % 256 == 0 && t256 >= 200) variant = 1;           // 256 x 256: least L2 traffic per flop
+        else if (Nout % 256 == 0 && 2 * t256 >= 128) variant = 3;  // 128 x 256: twice the workgroups
+        else variant = 2;
+    }
+    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, stream);
+    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, stream);
+    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, epilogue, out, stream);
+}
+
+}  // namespace
+
+int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int op_dtype,
+                     int variant, hipStream_t stream) {
+    if (M <= 0 || Nout <= 0) return RADIX_OK;
+    if (K <= 0) return RADIX_ERR_UNSUPPORTED;
+    if ((((uintptr_t)A | (uintptr_t)W | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
+    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, epilogue, out, variant, stream);
+    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, epilogue, out, variant, stream);
+    return RADIX_ERR_UNSUPPORTED;
+}

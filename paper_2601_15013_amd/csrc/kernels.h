@@ -23,13 +23,16 @@ void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* I
                         hipStream_t stream);
 // h[j, :] = (float) E[ids_c[j], :]
 void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int d, float* h, hipStream_t stream);
-// out[j, :] = h[j, :] * rsqrt(mean(h[j]^2) + eps) * g   (out in `out_dtype`: RADIX_F32 / RADIX_BF16)
+// out[j, :] = h[j, :] * rsqrt(mean(h[j]^2) + eps) * g   (out in `out_dtype`: RADIX_F32 / RADIX_BF16 / RADIX_F16)
 void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
                     hipStream_t stream);
 // In place on qkv[M, dq + 2 dkv]: per-head RMSNorm (optional) and RoPE of the q and k heads.
 void launch_qknorm_rope(void* qkv, int dtype, int M, int n_q_heads, int n_kv_heads, int hd, int qk_norm,
                         const float* gq, const float* gk, float eps, const int32_t* pos_c,
                         const float* cos_tab, const float* sin_tab, hipStream_t stream);
+
+// dst[i] = (f16) src[i] for n bf16 values (weights handed over as bf16, multiplied as fp16)
+void launch_bf16_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t stream);
 
 // ---- GEMMs: C[M, Nout] = A[M, K] * W[Nout, K]^T with an epilogue
 enum GemmEpilogue {
@@ -39,12 +42,14 @@ enum GemmEpilogue {
 };
 void launch_gemm_f32(const float* A, const float* W, int M, int Nout, int K, int epilogue, float* out_or_resid,
                      hipStream_t stream);
-int launch_gemm_bf16(const bf16_t* A, const bf16_t* W, int M, int Nout, int K, int epilogue, void* out_or_resid,
-                     hipStream_t stream);
+// 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), fp32 accumulate.  variant 0 = pick a tile shape.
+int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out_or_resid,
+                     int op_dtype, int variant, hipStream_t stream);
 
 // ---- causal varlen GQA attention on the full ragged layout.
 // qkv[N, dq + 2 dkv] rows hold q | k | v of one token; out[N, dq].
 void launch_attention_f32(const float* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                           int n_kv_heads, int hd, float* out, hipStream_t stream);
-int launch_attention_bf16(const bf16_t* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, bf16_t* out, hipStream_t stream);
+// 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), head_dim 128.
+int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream);

@@ -69,14 +69,14 @@ __global__ void interleave_gate_up_kernel(const uint4* __restrict__ wg, const ui
 
 __global__ void clear_status_kernel(int32_t* hdr) { hdr[0] = 0; }
 
-size_t esize(int dtype) { return dtype == RADIX_BF16 ? 2 : 4; }
+size_t esize(int dtype) { return dtype == RADIX_F32 ? 4 : 2; }
 
 struct WsLayout {
     size_t pos_full, ids_c, pos_c, h, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
 };
 
 WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
-    const size_t es = esize(c.dtype);
+    const size_t es = esize(c.compute_dtype);
     const size_t dq = (size_t)c.n_q_heads * c.head_dim, dkv = (size_t)c.n_kv_heads * c.head_dim;
     const size_t row = dq + 2 * dkv;
     const size_t M = N;                       // worst case: nothing is shared
@@ -105,11 +105,13 @@ int check_config(const radix_model_config& c) {
     if (c.n_q_heads % c.n_kv_heads != 0) return RADIX_ERR_BAD_CONFIG;
     if (!(c.eps >= 0.f) || !(c.rope_base > 0.f)) return RADIX_ERR_BAD_CONFIG;
     if (c.dtype != RADIX_F32 && c.dtype != RADIX_BF16) return RADIX_ERR_UNSUPPORTED;
+    if (c.dtype == RADIX_F32 && c.compute_dtype != RADIX_F32) return RADIX_ERR_UNSUPPORTED;
+    if (c.dtype == RADIX_BF16 && c.compute_dtype != RADIX_BF16 && c.compute_dtype != RADIX_F16) return RADIX_ERR_UNSUPPORTED;
     if (c.head_dim % 2 != 0 || c.head_dim > 128) return RADIX_ERR_UNSUPPORTED;
     if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
     if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
     if (c.dtype == RADIX_BF16) {
-        // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 64 and every
+        // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 32 and every
         // GEMM output width a multiple of 128
         const int dq = c.n_q_heads * c.head_dim, dkv = c.n_kv_heads * c.head_dim;
         if (c.head_dim != 128) return RADIX_ERR_UNSUPPORTED;
@@ -133,7 +135,7 @@ extern "C" int radix_model_create(const radix_model_config* config, const radix_
         if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wg || !w.wu || !w.wd) return RADIX_ERR_NULL_POINTER;
         if (c.qk_norm && (!w.gq || !w.gk)) return RADIX_ERR_NULL_POINTER;
     }
-    const size_t es = esize(c.dtype);
+    const size_t es = esize(c.dtype);       // weights are stored at their own width; 16-bit operand types share it
     const size_t d = c.d, hd = c.head_dim, dq = (size_t)c.n_q_heads * hd, dkv = (size_t)c.n_kv_heads * hd;
     const size_t di = c.d_int, half = hd / 2;
 
@@ -193,6 +195,11 @@ extern "C" int radix_model_create(const radix_model_config* config, const radix_
         if ((((uintptr_t)w.wg | (uintptr_t)w.wu) & 15) != 0) { ok = false; rc = RADIX_ERR_MISALIGNED; break; }
         hipLaunchKernelGGL(interleave_gate_up_kernel, dim3((unsigned)(2 * di)), dim3(256), 0, 0, (const uint4*)w.wg,
                            (const uint4*)w.wu, (int)di, row_vecs, (uint4*)(b + lo[l].wgu));
+        if (c.dtype == RADIX_BF16 && c.compute_dtype == RADIX_F16) {
+            // multiply in fp16: every bf16 weight of magnitude >= 2^-17 is represented exactly
+            const size_t first = lo[l].wqkv, last = lo[l].wd + d * di * es;
+            launch_bf16_to_f16((const bf16_t*)(b + first), (f16_t*)(b + first), (last - first) / 2, 0);
+        }
         radix_layer_dev& L = m->layers[l];
         L.g1 = (const float*)(b + lo[l].g1); L.g2 = (const float*)(b + lo[l].g2);
         L.gq = (const float*)(b + lo[l].gq); L.gk = (const float*)(b + lo[l].gk);
@@ -246,7 +253,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     if (N == 0) { HIP_TRY(hipGetLastError()); return RADIX_OK; }
     launch_validate_cu(cu, B, N, max_seqlen, hdr, stream);
 
-    const int dt = c.dtype;
+    const int dt = c.compute_dtype;          // activation / operand type
     const size_t es = esize(dt);
     const int d = c.d, hd = c.head_dim, dq = c.n_q_heads * hd, dkv = c.n_kv_heads * hd, row = dq + 2 * dkv;
     int32_t* pos_full = (int32_t*)(w + L.pos_full);
@@ -267,10 +274,10 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         pos = pos_full;
     }
     launch_compact_ids(tok, pos, dedup ? Ig : nullptr, M, N, c.vocab, c.max_pos, ids_c, pos_c, hdr, stream);
-    launch_embed(model->embed, dt, ids_c, M, d, h, stream);
+    launch_embed(model->embed, c.dtype, ids_c, M, d, h, stream);
 
     auto gemm = [&](const void* A, const void* W, int Nout, int K, int epi, void* o) -> int {
-        if (dt == RADIX_BF16) return launch_gemm_bf16((const bf16_t*)A, (const bf16_t*)W, M, Nout, K, epi, o, stream);
+        if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream);
         launch_gemm_f32((const float*)A, (const float*)W, M, Nout, K, epi, (float*)o, stream);
         return RADIX_OK;
     };
@@ -297,9 +304,9 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         {
             TimedScope t(RADIX_TIME_ATTENTION, stream);
-            if (dt == RADIX_BF16) {
-                rc = launch_attention_bf16((const bf16_t*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads,
-                                           hd, (bf16_t*)attn_full, stream);
+            if (dt != RADIX_F32) {
+                rc = launch_attention_mfma(qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd, attn_full,
+                                           dt, stream);
                 if (rc != RADIX_OK) return rc;
             } else {
                 launch_attention_f32((const float*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,

@@ -125,7 +125,20 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(T* __restrict__ qkv, i
     }
 }
 
+__global__ void bf16_to_f16_kernel(const bf16_t* src, f16_t* dst, size_t n) {   // may run in place
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = (f16_t)(float)src[i];
+}
+
 }  // namespace
+
+void launch_bf16_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t stream) {
+    if (n == 0) return;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(bf16_to_f16_kernel, dim3((unsigned)(blocks < 65536 ? blocks : 65536)), dim3(256), 0, stream, src,
+                       dst, n);
+}
 
 void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* idx, int n_rows, size_t row_bytes,
                               void* dst, int32_t* status, hipStream_t stream) {
@@ -174,6 +187,8 @@ void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, voi
     dim3 grid(ceil_div(M, 4)), block(256);
     if (out_dtype == RADIX_BF16)
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, grid, block, 0, stream, h, g, M, d, eps, (bf16_t*)out);
+    else if (out_dtype == RADIX_F16)
+        hipLaunchKernelGGL(rmsnorm_kernel<f16_t>, grid, block, 0, stream, h, g, M, d, eps, (f16_t*)out);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<float>, grid, block, 0, stream, h, g, M, d, eps, (float*)out);
 }
@@ -186,6 +201,9 @@ void launch_qknorm_rope(void* qkv, int dtype, int M, int n_q_heads, int n_kv_hea
     dim3 grid((unsigned)((items + 3) / 4)), block(256);
     if (dtype == RADIX_BF16)
         hipLaunchKernelGGL(qknorm_rope_kernel<bf16_t>, grid, block, 0, stream, (bf16_t*)qkv, M, n_q_heads, n_kv_heads,
+                           hd, qk_norm, gq, gk, eps, pos_c, cos_tab, sin_tab);
+    else if (dtype == RADIX_F16)
+        hipLaunchKernelGGL(qknorm_rope_kernel<f16_t>, grid, block, 0, stream, (f16_t*)qkv, M, n_q_heads, n_kv_heads,
                            hd, qk_norm, gq, gk, eps, pos_c, cos_tab, sin_tab);
     else
         hipLaunchKernelGGL(qknorm_rope_kernel<float>, grid, block, 0, stream, (float*)qkv, M, n_q_heads, n_kv_heads,

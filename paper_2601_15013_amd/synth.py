@@ -37,11 +37,16 @@ class ModelConfig:
     head_dim: int     # hd
     d_int: int        # SwiGLU intermediate size
     vocab: int
-    dtype: str        # "f32" or "bf16": storage type of weights and GEMM operands
+    dtype: str        # "f32" or "bf16": type the weights are generated, rounded and handed over in
     eps: float = 1e-6
     rope_base: float = 1e6
     qk_norm: bool = True
     max_pos: int = 4096
+    compute_dtype: str = ""   # operand type of the GPU path: "" = default ("f32", or "f16" for bf16 weights)
+
+    def __post_init__(self):
+        if not self.compute_dtype:
+            object.__setattr__(self, "compute_dtype", "f32" if self.dtype == "f32" else "f16")
 
     @property
     def dq(self) -> int:

@@ -1,8 +1,13 @@
 """GPU parity of the deduplicated / no-dedup prefill against the fp64 no-dedup oracle.
 
 Tolerances (max |err| over all outputs, relative to the RMS of the oracle's output):
-  fp32 configuration: 1e-4; bf16 configurations: 2e-2.
+  fp32 configuration: 1e-4;
+  bf16-weight configurations: 2e-2 with the default fp16 operands (fp32 accumulate);
+  with bf16 operands the 8-bit significand of every activation that feeds an MFMA costs about
+  0.57 % RMS / 2.9e-2 max over 28 layers (measured and reproduced by a CPU emulation of the
+  rounding points), so that mode is held to 5e-2.
 """
+import dataclasses
 import numpy as np
 import pytest
 import torch
@@ -13,7 +18,8 @@ from tests import gpu_util as U
 pytestmark = pytest.mark.gpu
 
 TOL_F32 = 1e-4
-TOL_BF16 = 2e-2
+TOL_BF16 = 2e-2          # bf16 weights, fp16 operands
+TOL_BF16_OPERANDS = 5e-2  # bf16 weights, bf16 operands
 
 
 def run_all(weights, batch, pos=None, **kw):
@@ -78,15 +84,31 @@ def test_fp32_no_qk_norm():
 SMALL_BF16 = synth.ModelConfig("bf16s", 3, 256, 4, 2, 128, 320, 2000, "bf16", max_pos=1024)
 
 
-def test_bf16_small_model_several_tiles_and_ragged_tail():
+@pytest.mark.parametrize("compute,tol", [("f16", TOL_BF16), ("bf16", TOL_BF16_OPERANDS)])
+def test_bf16_small_model_several_tiles_and_ragged_tail(compute, tol):
     # M = N' is not a multiple of any tile size; sequences span several attention tiles
-    w = synth.SynthWeights(SMALL_BF16, 31)
-    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab)
+    cfg = dataclasses.replace(SMALL_BF16, compute_dtype=compute)
+    w = synth.SynthWeights(cfg, 31)
+    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, cfg.vocab)
     y, y_nd, n_c = run_all(w, b)
     assert n_c == b.expected_n_compact and n_c % 32 != 0
     ref = U.oracle_rows(w, b)
-    assert U.rel_err(y_nd, ref) <= TOL_BF16
-    assert U.rel_err(y, ref) <= TOL_BF16
+    print(f"small bf16-weight model, {compute} operands: err dedup={U.rel_err(y, ref):.3e}")
+    assert U.rel_err(y_nd, ref) <= tol
+    assert U.rel_err(y, ref) <= tol
+    assert np.array_equal(y, y_nd)
+
+
+def test_bf16_wide_model_uses_large_gemm_tiles():
+    # enough rows and wide enough outputs for the 256x256 and 128x256 GEMM tiles, ragged M
+    cfg = synth.ModelConfig("bf16w", 2, 512, 8, 2, 128, 1536, 3000, "bf16", max_pos=1024)
+    w = synth.SynthWeights(cfg, 35)
+    b = synth.shared_prefix_batch(8, 40, 100, 150, 260, cfg.vocab)
+    y, y_nd, n_c = run_all(w, b)
+    assert n_c > 7000 and n_c % 256 != 0
+    ref = U.oracle_rows(w, b, sequences=[0, 7, 39])
+    rows = U.rows_of(b, [0, 7, 39])
+    assert U.rel_err(y[rows], ref) <= TOL_BF16
     assert np.array_equal(y, y_nd)
 
 
@@ -143,11 +165,13 @@ def test_empty_batch_and_bad_inputs():
     model.close()
 
 
-def _sampled_parity(key, sequences, tol=TOL_BF16):
+def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None):
     """Full-size batch on the GPU in the benchmark's launch configuration; the oracle computes
     whole sampled sequences (the no-dedup pass is independent per sequence)."""
     b = synth.make_batch(key)
     w = synth.make_weights(key)
+    if compute is not None:
+        w = synth.SynthWeights(dataclasses.replace(w.cfg, compute_dtype=compute), w.seed)
     y, y_nd, n_c = run_all(w, b, force_dedup=True)
     assert n_c == b.expected_n_compact
     rows = U.rows_of(b, sequences)
@@ -161,3 +185,7 @@ def _sampled_parity(key, sequences, tol=TOL_BF16):
 
 def test_c2_full_size_sampled_sequences():
     _sampled_parity("C2", [0, 17, 40, 63])
+
+
+def test_c2_full_size_bf16_operands():
+    _sampled_parity("C2", [0, 63], tol=TOL_BF16_OPERANDS, compute="bf16")
