@@ -2,8 +2,11 @@
 // softmax.  (Paper: Algorithm 1, "FlashAttn(q, k, v, cu_seqlens, causal=True)"; "Integration
 // with Attention": attention is the only step that needs all N rows.)
 //
-// One workgroup = 128 query rows of one (sequence, query head); 4 wavefronts x 32 queries.
-// Keys/values are walked in tiles of 64 staged in LDS.  Scores are produced TRANSPOSED,
+// One workgroup = 4 wavefronts x 32 queries working on ONE KV head: HPB query heads of its GQA
+// group (HPB = min(group, 4)) times 128 / HPB query rows, so the K/V tile staged in LDS is shared
+// by the query heads of the group and short sequences waste fewer empty query rows.
+// Keys/values are walked in tiles of 64 staged in LDS; the next tile's global loads are issued
+// before the current tile is multiplied, so their latency overlaps the MFMAs.  Scores are produced TRANSPOSED,
 // S^T[key, query] = K * Q^T with v_mfma_f32_32x32x16_{bf16,f16}, so that a lane owns one query column:
 // row maxima and sums are in-lane reductions plus one exchange with lane ^ 32, and the running
 // rescale factor is a per-lane scalar.  The second product is O^T[hd, query] = V^T * P^T, whose
@@ -16,12 +19,11 @@
 namespace {
 
 constexpr int HD = 128;
-constexpr int BQ = 128;     // queries per workgroup
 constexpr int BKV = 64;     // keys per tile
 constexpr int ATT_THREADS = 256;
 
-template <int DT>
-__global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
+template <int DT, int HPB>
+__global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
                                                                      const int32_t* __restrict__ cu, int N,
                                                                      int n_q_heads, int n_kv_heads, int n_qtiles,
                                                                      typename Op<DT>::T* __restrict__ out) {
@@ -31,7 +33,9 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typen
     __shared__ uint4 Ks[BKV * 16];          // [key][16 chunks of 8 hd], chunk ^= key & 15
     __shared__ uint32_t Vt[HD * 32];        // [hd][32 words of 2 keys], 8-byte chunk ^= (hd >> 1) & 15
 
-    const int seq = blockIdx.z, h = blockIdx.y;
+    constexpr int BQ = 128 / HPB;                       // query rows per workgroup
+    constexpr int WPH = 4 / HPB;                        // wavefronts per query head
+    const int seq = blockIdx.z;
     const int qt = n_qtiles - 1 - (int)blockIdx.x;      // heavy (late) tiles first
     // clamped so that a malformed cu_seqlens can never index outside the N rows
     int start = cu[seq], end = cu[seq + 1];
@@ -44,14 +48,16 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typen
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, g = lane >> 5;
     const int group = n_q_heads / n_kv_heads;
-    const int kvh = h / group;
+    const int h = (int)blockIdx.y * HPB + wave / WPH;   // query head of this wavefront
+    const int kvh = h / group;                          // same for all wavefronts: HPB divides group
+    const int wq = wave % WPH;                          // 32-row slice of the query tile
     const int dq = n_q_heads * HD, dkv = n_kv_heads * HD;
     const size_t row = (size_t)dq + 2 * (size_t)dkv;
     const T* kbase = qkv + (size_t)start * row + dq + (size_t)kvh * HD;
     const T* vbase = kbase + dkv;
 
     // ---- Q fragment (B operand of S^T = K Q^T): lane (n, g) holds Q[query n][16 ks + 8 g .. +8]
-    const int qi = q0 + wave * 32 + n;                  // query offset inside the sequence
+    const int qi = q0 + wq * 32 + n;                    // query offset inside the sequence
     const int qi_c = qi < len ? qi : len - 1;
     V8 qf[8];
     {
@@ -71,9 +77,33 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typen
     float m_run = -INFINITY, l_run = 0.f;
     const float sc = 1.4426950408889634f / sqrtf((float)HD);     // log2(e) / sqrt(hd)
 
-    const int wave_qmin = q0 + wave * 32, wave_qmax = wave_qmin + 31;
+    const int wave_qmin = q0 + wq * 32, wave_qmax = wave_qmin + 31;
     const int last_q = (q0 + BQ - 1) < (len - 1) ? (q0 + BQ - 1) : (len - 1);
     const int n_tiles = last_q / BKV + 1;
+
+    // global -> register loads of one K/V tile (rows past the end of the sequence are clamped; the
+    // causal mask hides them).  K: thread -> chunk tid % 16 of keys tid / 16 + 16 i.  V: lane -> key
+    // pair n, 8 hd columns c8 = wave * 4 + i * 2 + g, so that the transposed store packs 2 keys a word.
+    uint4 rk[4], rva[2], rvb[2];
+    auto load_tile = [&](int kv0) {
+        const int c = tid & 15;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int kr = kv0 + (tid >> 4) + 16 * i;
+            kr = kr < len ? kr : len - 1;
+            rk[i] = *((const uint4*)(kbase + (size_t)kr * row) + c);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c8 = wave * 4 + i * 2 + g;
+            int k0r = kv0 + 2 * n, k1r = k0r + 1;
+            k0r = k0r < len ? k0r : len - 1;
+            k1r = k1r < len ? k1r : len - 1;
+            rva[i] = *((const uint4*)(vbase + (size_t)k0r * row) + c8);
+            rvb[i] = *((const uint4*)(vbase + (size_t)k1r * row) + c8);
+        }
+    };
+    load_tile(0);
 
     for (int t = 0; t < n_tiles; ++t) {
         const int kv0 = t * BKV;
@@ -84,20 +114,13 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typen
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int key = (tid >> 4) + 16 * i;
-                int kr = kv0 + key;
-                kr = kr < len ? kr : len - 1;
-                uint4 v = *((const uint4*)(kbase + (size_t)kr * row) + c);
-                Ks[key * 16 + (c ^ (key & 15))] = v;
+                Ks[key * 16 + (c ^ (key & 15))] = rk[i];
             }
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const int c8 = wave * 4 + i * 2 + g;            // which 8 hd columns
-                int k0r = kv0 + 2 * n, k1r = k0r + 1;
-                k0r = k0r < len ? k0r : len - 1;
-                k1r = k1r < len ? k1r : len - 1;
-                uint4 a = *((const uint4*)(vbase + (size_t)k0r * row) + c8);
-                uint4 b = *((const uint4*)(vbase + (size_t)k1r * row) + c8);
-                const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+                const int c8 = wave * 4 + i * 2 + g;
+                const uint32_t aw[4] = {rva[i].x, rva[i].y, rva[i].z, rva[i].w};
+                const uint32_t bw[4] = {rvb[i].x, rvb[i].y, rvb[i].z, rvb[i].w};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t lo = (aw[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
@@ -108,6 +131,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_mfma_kernel(const typen
             }
         }
         __syncthreads();
+        if (t + 1 < n_tiles) load_tile(kv0 + BKV);     // in flight while this tile is multiplied
         if (kv0 > wave_qmax) continue;          // whole tile is in this wavefront's future
 
         // ---- S^T = K Q^T : two 32-key blocks
@@ -197,15 +221,19 @@ int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int 
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
     if (max_seqlen <= 0) return RADIX_ERR_BAD_SIZE;
     if (B > 65535 || n_q_heads > 65535) return RADIX_ERR_UNSUPPORTED;
-    const int n_qtiles = ceil_div(max_seqlen, BQ);
-    const dim3 grid(n_qtiles, n_q_heads, B), block(ATT_THREADS);
-    if (op_dtype == RADIX_BF16)
-        hipLaunchKernelGGL(attention_mfma_kernel<RADIX_BF16>, grid, block, 0, stream, (const bf16_t*)qkv, cu, N,
-                           n_q_heads, n_kv_heads, n_qtiles, (bf16_t*)out);
-    else if (op_dtype == RADIX_F16)
-        hipLaunchKernelGGL(attention_mfma_kernel<RADIX_F16>, grid, block, 0, stream, (const f16_t*)qkv, cu, N,
-                           n_q_heads, n_kv_heads, n_qtiles, (f16_t*)out);
-    else
-        return RADIX_ERR_UNSUPPORTED;
+    if (op_dtype != RADIX_BF16 && op_dtype != RADIX_F16) return RADIX_ERR_UNSUPPORTED;
+    const int group = n_q_heads / n_kv_heads;
+    const int hpb = (group % 4 == 0) ? 4 : (group % 2 == 0 ? 2 : 1);    // query heads per workgroup
+    const int n_qtiles = ceil_div(max_seqlen, 128 / hpb);
+    const dim3 grid(n_qtiles, n_q_heads / hpb, B), block(ATT_THREADS);
+#define RADIX_ATT(DT, HPB)                                                                                       \
+    hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,   \
+                       n_q_heads, n_kv_heads, n_qtiles, (Op<DT>::T*)out)
+    if (op_dtype == RADIX_BF16) {
+        if (hpb == 4) RADIX_ATT(RADIX_BF16, 4); else if (hpb == 2) RADIX_ATT(RADIX_BF16, 2); else RADIX_ATT(RADIX_BF16, 1);
+    } else {
+        if (hpb == 4) RADIX_ATT(RADIX_F16, 4); else if (hpb == 2) RADIX_ATT(RADIX_F16, 2); else RADIX_ATT(RADIX_F16, 1);
+    }
+#undef RADIX_ATT
     return RADIX_OK;
 }

@@ -64,7 +64,7 @@ template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename Op<DT>::T* __restrict__ A,
                                                                  const typename Op<DT>::T* __restrict__ W, int M,
                                                                  int Nout, int K, void* __restrict__ out_,
-                                                                 int tiles_m, int tiles_n) {
+                                                                 int tiles_m, int tiles_n, QkvEpilogue qe) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
@@ -75,6 +75,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int LOADS = A_LOADS + B_LOADS;
     constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
     static_assert(EPI != EPI_SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
+    static_assert(EPI != EPI_QKV_ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
     static_assert(LOADS * 3 < 64, "vmcnt range");
 
     constexpr int EPI_PITCH = 272;                             // epilogue row pitch in bytes (256 + 16 pad)
@@ -268,6 +269,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         const int orow = lane / CHUNKS, ochunk = lane % CHUNKS;
         const int ldo = (EPI == EPI_SWIGLU) ? (Nout >> 1) : Nout;
         const int ncol0 = (EPI == EPI_SWIGLU) ? ((n0 + wn * WTN) >> 1) : (n0 + wn * WTN);
+        // EPI_QKV_ROPE: which head this wavefront's columns are, and whether it is rotated (q, k) or not (v)
+        const int head = (n0 + wn * WTN) >> 7;
+        const bool rope_head = EPI == EPI_QKV_ROPE && head < qe.n_q_heads + qe.n_kv_heads;
+        const float* rope_gain = (EPI == EPI_QKV_ROPE && head >= qe.n_q_heads) ? qe.gk : qe.gq;
 #pragma unroll
         for (int ip = 0; ip < MB; ip += 2) {
 #pragma unroll
@@ -286,6 +291,52 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                             }
                             *reinterpret_cast<V4*>(rowp + ((j >> 1) * 32 + 8 * q + 4 * g) * 2) = v;
                         }
+                } else if (EPI == EPI_QKV_ROPE && rope_head) {
+                    // This wavefront's 128 columns are exactly one q or k head of the fused q|k|v row and
+                    // a lane owns a row: the per-head RMSNorm is an in-lane sum of 64 squares plus one
+                    // exchange with lane ^ 32, and the rotary partner of column c < 64 (block j) is
+                    // column c + 64 (block j + 2) of the same lane and register.  (Paper: Q/K norms and
+                    // RoPE are position-wise, hence run on compact rows - "Integration with Attention".)
+                    const int i = ip + il;
+                    int gm = m0 + wm * WTM + i * 32 + r;
+                    gm = gm < M ? gm : M - 1;
+                    float rs = 1.0f;
+                    if (qe.qk_norm) {
+                        float ss = 0.f;
+#pragma unroll
+                        for (int j = 0; j < NB; ++j)
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) ss += acc[j][i][e] * acc[j][i][e];
+                        ss += __shfl_xor(ss, 32, 64);
+                        rs = 1.0f / sqrtf(ss * (1.0f / 128.0f) + qe.eps);
+                    }
+                    const int p = qe.pos_c[gm];
+                    const float* ct = qe.cos_tab + (size_t)p * 64;
+                    const float* st = qe.sin_tab + (size_t)p * 64;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int c = 32 * j + 8 * q + 4 * g;
+                            const f32x4 cs = *reinterpret_cast<const f32x4*>(ct + c);
+                            const f32x4 sn = *reinterpret_cast<const f32x4*>(st + c);
+                            f32x4 ga = {1.f, 1.f, 1.f, 1.f}, gb = {1.f, 1.f, 1.f, 1.f};
+                            if (qe.qk_norm) {
+                                ga = *reinterpret_cast<const f32x4*>(rope_gain + c);
+                                gb = *reinterpret_cast<const f32x4*>(rope_gain + c + 64);
+                            }
+                            V4 va, vb;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const float xa = acc[j][i][q * 4 + t] * rs * ga[t];
+                                const float xb = acc[j + 2][i][q * 4 + t] * rs * gb[t];
+                                va[t] = (T)(xa * cs[t] - xb * sn[t]);
+                                vb[t] = (T)(xb * cs[t] + xa * sn[t]);
+                            }
+                            *reinterpret_cast<V4*>(rowp + c * 2) = va;
+                            *reinterpret_cast<V4*>(rowp + (c + 64) * 2) = vb;
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
                 } else {
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
@@ -310,7 +361,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 }
 
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
-int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, hipStream_t stream) {
+int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, const QkvEpilogue& qe,
+               hipStream_t stream) {
     typedef typename Op<DT>::T T;
     if (Nout % BN != 0 || K % BK != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
@@ -319,38 +371,48 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogu
     do {                                                                                                      \
         auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
         hipLaunchKernelGGL(kfn, grid, block, 0, stream, (const T*)A, (const T*)W, M, Nout, K, out, tiles_m,   \
-                           tiles_n);                                                                          \
+                           tiles_n, qe);                                                                      \
     } while (0)
     if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
     else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
-    else RADIX_LAUNCH(EPI_SWIGLU);
+    else if (epilogue == EPI_SWIGLU) RADIX_LAUNCH(EPI_SWIGLU);
+    else if (epilogue == EPI_QKV_ROPE) {
+        if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_QKV_ROPE);
+        else return RADIX_ERR_UNSUPPORTED;
+    } else return RADIX_ERR_UNSUPPORTED;
 #undef RADIX_LAUNCH
     return RADIX_OK;
 }
 
 template <int DT>
 int launch_dt(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int variant,
-              hipStream_t stream) {
+              const QkvEpilogue& qe, hipStream_t stream) {
     // tile choice: the biggest tile that still gives every CU work
     const long long t256 = (long long)ceil_div(M, 256) * (Nout / 256);
     if (variant == 0) {
         if (Nout % 256 == 0 && t256 >= 200) variant = 1;           // 256 x 256: least L2 traffic per flop
         else if (Nout % 256 == 0 && 2 * t256 >= 128) variant = 3;  // 128 x 256: twice the workgroups
         else variant = 2;
+        if (epilogue == EPI_QKV_ROPE && variant == 2) variant = 3;   // needs 128-wide wavefront blocks
     }
-    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, stream);
-    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, stream);
-    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, epilogue, out, stream);
+    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, qe, stream);
+    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, qe, stream);
+    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, epilogue, out, qe, stream);
 }
 
 }  // namespace
 
 int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int op_dtype,
-                     int variant, hipStream_t stream) {
+                     int variant, hipStream_t stream, const QkvEpilogue* qkv) {
     if (M <= 0 || Nout <= 0) return RADIX_OK;
     if (K <= 0) return RADIX_ERR_UNSUPPORTED;
     if ((((uintptr_t)A | (uintptr_t)W | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
-    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, epilogue, out, variant, stream);
-    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, epilogue, out, variant, stream);
+    QkvEpilogue qe = {};
+    if (epilogue == EPI_QKV_ROPE) {
+        if (!qkv || Nout % 256 != 0) return RADIX_ERR_UNSUPPORTED;
+        qe = *qkv;
+    }
+    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, epilogue, out, variant, qe, stream);
+    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, epilogue, out, variant, qe, stream);
     return RADIX_ERR_UNSUPPORTED;
 }

@@ -38,13 +38,24 @@ void launch_bf16_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t str
 enum GemmEpilogue {
     EPI_STORE = 0,     // C stored in the activation dtype
     EPI_RESIDUAL = 1,  // resid[M, Nout] (fp32) += C
-    EPI_SWIGLU = 2     // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
+    EPI_SWIGLU = 2,    // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
+    EPI_QKV_ROPE = 3   // EPI_STORE of the fused q|k|v row with per-head RMSNorm and RoPE applied to q and k heads
+};
+// Extra inputs of EPI_QKV_ROPE (head_dim 128): gains and tables are device pointers.
+struct QkvEpilogue {
+    const float* gq;        // [128] q-norm gain
+    const float* gk;        // [128] k-norm gain
+    const float* cos_tab;   // [max_pos, 64]
+    const float* sin_tab;   // [max_pos, 64]
+    const int32_t* pos_c;   // [M] position id of every row
+    int n_q_heads, n_kv_heads, qk_norm;
+    float eps;
 };
 void launch_gemm_f32(const float* A, const float* W, int M, int Nout, int K, int epilogue, float* out_or_resid,
                      hipStream_t stream);
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), fp32 accumulate.  variant 0 = pick a tile shape.
 int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out_or_resid,
-                     int op_dtype, int variant, hipStream_t stream);
+                     int op_dtype, int variant, hipStream_t stream, const QkvEpilogue* qkv = nullptr);
 
 // ---- causal varlen GQA attention on the full ragged layout.
 // qkv[N, dq + 2 dkv] rows hold q | k | v of one token; out[N, dq].

@@ -289,11 +289,20 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
             TimedScope t(RADIX_TIME_ROWOPS, stream);
             launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
         }
+        // Q/K-norm and RoPE ride in the QKV GEMM's epilogue when a wavefront block is one head
+        const bool fused_rope = dt != RADIX_F32 && hd == 128 && row % 256 == 0;
         {
             TimedScope t(RADIX_TIME_GEMM_QKV, stream);
-            if ((rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv)) != RADIX_OK) return rc;
+            if (fused_rope) {
+                const QkvEpilogue qe = {Lw.gq, Lw.gk, model->cos_tab, model->sin_tab, pos_c,
+                                        c.n_q_heads, c.n_kv_heads, c.qk_norm, c.eps};
+                rc = launch_gemm_mfma(a, Lw.wqkv, M, row, d, EPI_QKV_ROPE, qkv, dt, 0, stream, &qe);
+            } else {
+                rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv);
+            }
+            if (rc != RADIX_OK) return rc;
         }
-        {
+        if (!fused_rope) {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
             launch_qknorm_rope(qkv, dt, M, c.n_q_heads, c.n_kv_heads, hd, c.qk_norm, Lw.gq, Lw.gk, c.eps, pos_c,
                                model->cos_tab, model->sin_tab, stream);

@@ -92,6 +92,54 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     for (int c = lane; c < d; c += 64) o[c] = from_f32<T>(x[c] * r * g[c]);
 }
 
+// Same, for d = 256 NV: the row stays in registers (NV float4 per lane), so it is read once, with
+// 16-byte accesses on both sides.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_vec_kernel(const float* __restrict__ h, const float* __restrict__ g,
+                                                          int M, float eps, T* __restrict__ out) {
+    constexpr int d = 256 * NV;
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const f32x4* x = reinterpret_cast<const f32x4*>(h + (size_t)row * d);
+    f32x4 v[NV];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        v[k] = x[lane + 64 * k];
+        ss += v[k][0] * v[k][0] + v[k][1] * v[k][1] + v[k][2] * v[k][2] + v[k][3] * v[k][3];
+    }
+    ss = wave_sum(ss);
+    const float r = 1.0f / sqrtf(ss / (float)d + eps);
+    const f32x4* gv = reinterpret_cast<const f32x4*>(g);
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        const f32x4 gg = gv[lane + 64 * k];
+        T o4[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) o4[t] = from_f32<T>(v[k][t] * r * gg[t]);
+        T* o = out + (size_t)row * d + 4 * (lane + 64 * k);
+        if (sizeof(T) == 4) {
+            *reinterpret_cast<uint4*>(o) = *reinterpret_cast<uint4*>(o4);
+        } else {
+            *reinterpret_cast<uint2*>(o) = *reinterpret_cast<uint2*>(o4);
+        }
+    }
+}
+
+template <typename T>
+bool launch_rmsnorm_vec(const float* h, const float* g, int M, int d, float eps, T* out, hipStream_t stream) {
+    if (d % 256 != 0 || (((uintptr_t)h | (uintptr_t)g | (uintptr_t)out) & 15) != 0) return false;
+    dim3 grid(ceil_div(M, 4)), block(256);
+    switch (d / 256) {
+#define RADIX_CASE(NV) case NV: hipLaunchKernelGGL((rmsnorm_vec_kernel<T, NV>), grid, block, 0, stream, h, g, M, eps, out); return true;
+        RADIX_CASE(1) RADIX_CASE(2) RADIX_CASE(3) RADIX_CASE(4) RADIX_CASE(5) RADIX_CASE(6) RADIX_CASE(8) RADIX_CASE(10)
+        RADIX_CASE(12) RADIX_CASE(16) RADIX_CASE(20) RADIX_CASE(32)
+#undef RADIX_CASE
+        default: return false;
+    }
+}
+
 // One wavefront per (row, head); lane i < hd/2 owns the rotary pair (i, i + hd/2).
 template <typename T>
 __global__ __launch_bounds__(256) void qknorm_rope_kernel(T* __restrict__ qkv, int M, int n_q_heads, int n_kv_heads,
@@ -184,6 +232,9 @@ void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int
 void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
                     hipStream_t stream) {
     if (M <= 0) return;
+    if (out_dtype == RADIX_BF16 && launch_rmsnorm_vec(h, g, M, d, eps, (bf16_t*)out, stream)) return;
+    if (out_dtype == RADIX_F16 && launch_rmsnorm_vec(h, g, M, d, eps, (f16_t*)out, stream)) return;
+    if (out_dtype == RADIX_F32 && launch_rmsnorm_vec(h, g, M, d, eps, (float*)out, stream)) return;
     dim3 grid(ceil_div(M, 4)), block(256);
     if (out_dtype == RADIX_BF16)
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, grid, block, 0, stream, h, g, M, d, eps, (bf16_t*)out);

@@ -187,5 +187,25 @@ def test_c2_full_size_sampled_sequences():
     _sampled_parity("C2", [0, 17, 40, 63])
 
 
+def test_c3_full_size_sampled_sequences():
+    # 4B shape, three-level trie (1 -> 8 -> 128): first and last sequence and one from the middle groups
+    _sampled_parity("C3", [0, 70, 127])
+
+
+def test_c4_full_size_sampled_sequences():
+    # 8B shape, 256 sequences
+    _sampled_parity("C4", [0, 255])
+
+
+def test_c5_full_size_sampled_sequences():
+    # long shared prefix: 2080-token sequences, ~43x compression
+    _sampled_parity("C5", [0, 127])
+
+
+def test_c5_control_batch_no_sharing():
+    # same token count, nothing shared, deduplication forced on: identity maps, M = N
+    _sampled_parity("C5ctl", [3])
+
+
 def test_c2_full_size_bf16_operands():
     _sampled_parity("C2", [0, 63], tol=TOL_BF16_OPERANDS, compute="bf16")
