@@ -37,7 +37,7 @@ class RadixError(RuntimeError):
 
 class radix_model_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d", "n_q_heads", "n_kv_heads", "head_dim", "d_int", "vocab",
-                                          "max_pos", "qk_norm", "dtype", "compute_dtype")] + [("eps", C.c_float), ("rope_base", C.c_float)]
+                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "split_norm_out")] + [("eps", C.c_float), ("rope_base", C.c_float)]
 
 
 class radix_layer_weights(C.Structure):
@@ -133,8 +133,8 @@ def make_config(cfg: Any) -> radix_model_config:
     """cfg: any object with the ModelConfig attributes (n_layers, d, n_q_heads, ...)."""
     compute = getattr(cfg, "compute_dtype", None) or cfg.dtype
     return radix_model_config(cfg.n_layers, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_int, cfg.vocab,
-                              cfg.max_pos, int(cfg.qk_norm), _DTYPES[cfg.dtype], _DTYPES[compute], cfg.eps,
-                              cfg.rope_base)
+                              cfg.max_pos, int(cfg.qk_norm), _DTYPES[cfg.dtype], _DTYPES[compute],
+                              int(getattr(cfg, "split_norm_out", 0)), cfg.eps, cfg.rope_base)
 
 
 def radix_model_create(cfg: Any, embed: torch.Tensor, gf: torch.Tensor,

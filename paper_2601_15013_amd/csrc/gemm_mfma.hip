@@ -64,7 +64,8 @@ template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename Op<DT>::T* __restrict__ A,
                                                                  const typename Op<DT>::T* __restrict__ W, int M,
                                                                  int Nout, int K, void* __restrict__ out_,
-                                                                 int tiles_m, int tiles_n, QkvEpilogue qe) {
+                                                                 int tiles_m, int tiles_n, int w_k,
+                                                                 QkvEpilogue qe) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
@@ -123,10 +124,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j) {
         const int row = 16 * (wave + 4 * j) + lrow;
-        w_off[j] = (uint32_t)(((size_t)row * K + 8 * (lpc ^ swz(row))) * sizeof(T));
+        w_off[j] = (uint32_t)(((size_t)row * w_k + 8 * (lpc ^ swz(row))) * sizeof(T));
     }
     const char* a_base = (const char*)(A + (size_t)m0 * K);
-    const char* w_base = (const char*)(W + (size_t)n0 * K);
+    const char* w_base = (const char*)(W + (size_t)n0 * w_k);
+    const int WKT = w_k / BK;       // k-tiles in a weight row; tiles past it wrap (A = [hi | lo] mode)
 
     f32x16 acc[NB][MB];
 #pragma unroll
@@ -151,19 +153,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         }                                                                                                          \
     } while (0)
 
-#define RADIX_DMA1(KB, ST, F)                                                                                      \
+#define RADIX_DMA1(KT_, ST, F)                                                                                     \
     do {                                                                                                           \
         if ((F) < A_LOADS)                                                                                         \
-            dma16(a_base + (KB), a_off[(F) < A_LOADS ? (F) : 0], lds_addr((ST) + 64 * (wave + 4 * (F))));          \
+            dma16(a_base + (size_t)(KT_) * (BK * sizeof(T)), a_off[(F) < A_LOADS ? (F) : 0],                       \
+                  lds_addr((ST) + 64 * (wave + 4 * (F))));                                                         \
         else if ((F) < LOADS)                                                                                      \
-            dma16(w_base + (KB), w_off[(F) >= A_LOADS && (F) < LOADS ? (F) - A_LOADS : 0],                         \
+            dma16(w_base + (size_t)((KT_) >= WKT ? (KT_) - WKT : (KT_)) * (BK * sizeof(T)),                        \
+                  w_off[(F) >= A_LOADS && (F) < LOADS ? (F) - A_LOADS : 0],                                        \
                   lds_addr((ST) + BM * 4 + 64 * (wave + 4 * ((F) - A_LOADS))));                                    \
     } while (0)
 
 #define RADIX_ISSUE(TILE, ST)                                                                                      \
     do {                                                                                                           \
-        const size_t kb_ = (size_t)((TILE) < KT ? (TILE) : KT - 1) * (BK * sizeof(T));                             \
-        _Pragma("unroll") for (int f = 0; f < LOADS; ++f) RADIX_DMA1(kb_, ST, f);                                  \
+        const int kt__ = (TILE) < KT ? (TILE) : KT - 1;                                                            \
+        _Pragma("unroll") for (int f = 0; f < LOADS; ++f) RADIX_DMA1(kt__, ST, f);                                 \
     } while (0)
 
     // MFMAs [lo, hi) of the MB x NB block products of one k-step, in (j, i) order
@@ -194,9 +198,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         wait_vmcnt<LOADS>();                                                                       \
         __builtin_amdgcn_s_barrier();                                                              \
         {                                                                                          \
-            const size_t kb_ = (size_t)(kt + (O) + 3 < KT ? kt + (O) + 3 : KT - 1) * (BK * sizeof(T)); \
+            const int kt__ = kt + (O) + 3 < KT ? kt + (O) + 3 : KT - 1;                            \
             _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                    \
-                RADIX_DMA1(kb_, REFILL, u);                                                        \
+                RADIX_DMA1(kt__, REFILL, u);                                                       \
                 RADIX_FRAG1(NXT, 0, fa0, fb0, u);                                                  \
                 RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);              \
                 __builtin_amdgcn_sched_barrier(0);                                                 \
@@ -361,8 +365,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 }
 
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
-int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, const QkvEpilogue& qe,
-               hipStream_t stream) {
+int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out,
+               const QkvEpilogue& qe, hipStream_t stream) {
     typedef typename Op<DT>::T T;
     if (Nout % BN != 0 || K % BK != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
@@ -371,7 +375,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogu
     do {                                                                                                      \
         auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
         hipLaunchKernelGGL(kfn, grid, block, 0, stream, (const T*)A, (const T*)W, M, Nout, K, out, tiles_m,   \
-                           tiles_n, qe);                                                                      \
+                           tiles_n, w_k, qe);                                                                 \
     } while (0)
     if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
     else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
@@ -385,7 +389,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int epilogu
 }
 
 template <int DT>
-int launch_dt(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int variant,
+int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out, int variant,
               const QkvEpilogue& qe, hipStream_t stream) {
     // tile choice: the biggest tile that still gives every CU work
     const long long t256 = (long long)ceil_div(M, 256) * (Nout / 256);
@@ -395,24 +399,26 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int epilogue
         else variant = 2;
         if (epilogue == EPI_QKV_ROPE && variant == 2) variant = 3;   // needs 128-wide wavefront blocks
     }
-    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, qe, stream);
-    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, epilogue, out, qe, stream);
-    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, epilogue, out, qe, stream);
+    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
+    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
+    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
 }
 
 }  // namespace
 
 int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int op_dtype,
-                     int variant, hipStream_t stream, const QkvEpilogue* qkv) {
+                     int variant, hipStream_t stream, const QkvEpilogue* qkv, int w_k) {
     if (M <= 0 || Nout <= 0) return RADIX_OK;
     if (K <= 0) return RADIX_ERR_UNSUPPORTED;
+    if (w_k == 0) w_k = K;
+    if (w_k != K && (2 * w_k != K || w_k % 32 != 0)) return RADIX_ERR_UNSUPPORTED;
     if ((((uintptr_t)A | (uintptr_t)W | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
     QkvEpilogue qe = {};
     if (epilogue == EPI_QKV_ROPE) {
         if (!qkv || Nout % 256 != 0) return RADIX_ERR_UNSUPPORTED;
         qe = *qkv;
     }
-    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, epilogue, out, variant, qe, stream);
-    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, epilogue, out, variant, qe, stream);
+    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, stream);
+    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, stream);
     return RADIX_ERR_UNSUPPORTED;
 }

@@ -26,6 +26,10 @@ void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int
 // out[j, :] = h[j, :] * rsqrt(mean(h[j]^2) + eps) * g   (out in `out_dtype`: RADIX_F32 / RADIX_BF16 / RADIX_F16)
 void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
                     hipStream_t stream);
+// out[j, 0:d] = T(y), out[j, d:2d] = T(y - T(y)) with y the RMSNorm above: a hi/lo pair of 16-bit values
+// (out_dtype RADIX_BF16 / RADIX_F16, d a multiple of 256).
+int launch_rmsnorm_split(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
+                         hipStream_t stream);
 // In place on qkv[M, dq + 2 dkv]: per-head RMSNorm (optional) and RoPE of the q and k heads.
 void launch_qknorm_rope(void* qkv, int dtype, int M, int n_q_heads, int n_kv_heads, int hd, int qk_norm,
                         const float* gq, const float* gk, float eps, const int32_t* pos_c,
@@ -54,8 +58,10 @@ struct QkvEpilogue {
 void launch_gemm_f32(const float* A, const float* W, int M, int Nout, int K, int epilogue, float* out_or_resid,
                      hipStream_t stream);
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), fp32 accumulate.  variant 0 = pick a tile shape.
+// w_k: row length of W.  w_k == K is the plain product; w_k == K / 2 multiplies A = [hi | lo] against
+// the weights repeated twice along k, i.e. C = (hi + lo) * W^T.
 int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out_or_resid,
-                     int op_dtype, int variant, hipStream_t stream, const QkvEpilogue* qkv = nullptr);
+                     int op_dtype, int variant, hipStream_t stream, const QkvEpilogue* qkv = nullptr, int w_k = 0);
 
 // ---- causal varlen GQA attention on the full ragged layout.
 // qkv[N, dq + 2 dkv] rows hold q | k | v of one token; out[N, dq].

@@ -87,7 +87,7 @@ WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
     L.ids_c = take(M * 4);
     L.pos_c = take(M * 4);
     L.h = take(M * c.d * 4);
-    L.a = take(M * c.d * es);
+    L.a = take(M * c.d * es * (c.split_norm_out ? 2 : 1));
     L.qkv = take(M * row * es);
     L.qkv_full = take(N * row * es);
     L.attn_full = take(N * dq * es);
@@ -110,6 +110,8 @@ int check_config(const radix_model_config& c) {
     if (c.head_dim % 2 != 0 || c.head_dim > 128) return RADIX_ERR_UNSUPPORTED;
     if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
     if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
+    if (c.split_norm_out != 0 && c.split_norm_out != 1) return RADIX_ERR_BAD_CONFIG;
+    if (c.split_norm_out && (c.dtype != RADIX_BF16 || c.d % 256 != 0)) return RADIX_ERR_UNSUPPORTED;
     if (c.dtype == RADIX_BF16) {
         // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 32 and every
         // GEMM output width a multiple of 128
@@ -285,9 +287,14 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     int rc = RADIX_OK;
     for (int l = 0; l < c.n_layers; ++l) {
         const radix_layer_dev& Lw = model->layers[l];
+        const int ka = c.split_norm_out ? 2 * d : d;     // K of the GEMMs fed by an RMSNorm
         {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
-            launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
+            if (c.split_norm_out) {
+                if ((rc = launch_rmsnorm_split(h, Lw.g1, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
+            } else {
+                launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
+            }
         }
         // Q/K-norm and RoPE ride in the QKV GEMM's epilogue when a wavefront block is one head
         const bool fused_rope = dt != RADIX_F32 && hd == 128 && row % 256 == 0;
@@ -296,7 +303,9 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
             if (fused_rope) {
                 const QkvEpilogue qe = {Lw.gq, Lw.gk, model->cos_tab, model->sin_tab, pos_c,
                                         c.n_q_heads, c.n_kv_heads, c.qk_norm, c.eps};
-                rc = launch_gemm_mfma(a, Lw.wqkv, M, row, d, EPI_QKV_ROPE, qkv, dt, 0, stream, &qe);
+                rc = launch_gemm_mfma(a, Lw.wqkv, M, row, ka, EPI_QKV_ROPE, qkv, dt, 0, stream, &qe, d);
+            } else if (dt != RADIX_F32) {
+                rc = launch_gemm_mfma(a, Lw.wqkv, M, row, ka, EPI_STORE, qkv, dt, 0, stream, nullptr, d);
             } else {
                 rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv);
             }
@@ -332,11 +341,19 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
-            launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
+            if (c.split_norm_out) {
+                if ((rc = launch_rmsnorm_split(h, Lw.g2, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
+            } else {
+                launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
+            }
         }
         {
             TimedScope t(RADIX_TIME_GEMM_GATEUP, stream);
-            if ((rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp)) != RADIX_OK) return rc;
+            if (dt != RADIX_F32)
+                rc = launch_gemm_mfma(a, Lw.wgu, M, 2 * c.d_int, ka, EPI_SWIGLU, mlp, dt, 0, stream, nullptr, d);
+            else
+                rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp);
+            if (rc != RADIX_OK) return rc;
         }
         {
             TimedScope t(RADIX_TIME_GEMM_DOWN, stream);

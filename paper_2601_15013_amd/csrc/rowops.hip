@@ -94,7 +94,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
 
 // Same, for d = 256 NV: the row stays in registers (NV float4 per lane), so it is read once, with
 // 16-byte accesses on both sides.
-template <typename T, int NV>
+// SPLIT: the row is written as [hi | lo] (2 d values) with hi = T(y) and lo = T(y - hi), so that a GEMM
+// over the doubled K against the weights repeated twice sees the activation to ~2x the significand.
+template <typename T, int NV, bool SPLIT>
 __global__ __launch_bounds__(256) void rmsnorm_vec_kernel(const float* __restrict__ h, const float* __restrict__ g,
                                                           int M, float eps, T* __restrict__ out) {
     constexpr int d = 256 * NV;
@@ -115,24 +117,29 @@ __global__ __launch_bounds__(256) void rmsnorm_vec_kernel(const float* __restric
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
         const f32x4 gg = gv[lane + 64 * k];
-        T o4[4];
+        T o4[4], l4[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) o4[t] = from_f32<T>(v[k][t] * r * gg[t]);
-        T* o = out + (size_t)row * d + 4 * (lane + 64 * k);
+        for (int t = 0; t < 4; ++t) {
+            const float y = v[k][t] * r * gg[t];
+            o4[t] = from_f32<T>(y);
+            l4[t] = from_f32<T>(y - to_f32<T>(o4[t]));
+        }
+        T* o = out + (size_t)row * (SPLIT ? 2 * d : d) + 4 * (lane + 64 * k);
         if (sizeof(T) == 4) {
             *reinterpret_cast<uint4*>(o) = *reinterpret_cast<uint4*>(o4);
         } else {
             *reinterpret_cast<uint2*>(o) = *reinterpret_cast<uint2*>(o4);
+            if (SPLIT) *reinterpret_cast<uint2*>(o + d) = *reinterpret_cast<uint2*>(l4);
         }
     }
 }
 
-template <typename T>
+template <typename T, bool SPLIT>
 bool launch_rmsnorm_vec(const float* h, const float* g, int M, int d, float eps, T* out, hipStream_t stream) {
     if (d % 256 != 0 || (((uintptr_t)h | (uintptr_t)g | (uintptr_t)out) & 15) != 0) return false;
     dim3 grid(ceil_div(M, 4)), block(256);
     switch (d / 256) {
-#define RADIX_CASE(NV) case NV: hipLaunchKernelGGL((rmsnorm_vec_kernel<T, NV>), grid, block, 0, stream, h, g, M, eps, out); return true;
+#define RADIX_CASE(NV) case NV: hipLaunchKernelGGL((rmsnorm_vec_kernel<T, NV, SPLIT>), grid, block, 0, stream, h, g, M, eps, out); return true;
         RADIX_CASE(1) RADIX_CASE(2) RADIX_CASE(3) RADIX_CASE(4) RADIX_CASE(5) RADIX_CASE(6) RADIX_CASE(8) RADIX_CASE(10)
         RADIX_CASE(12) RADIX_CASE(16) RADIX_CASE(20) RADIX_CASE(32)
 #undef RADIX_CASE
@@ -229,12 +236,20 @@ void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int
         hipLaunchKernelGGL(embed_kernel<float>, grid, block, 0, stream, (const float*)embed, ids_c, M, d, h);
 }
 
+int launch_rmsnorm_split(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
+                         hipStream_t stream) {
+    if (M <= 0) return RADIX_OK;
+    if (out_dtype == RADIX_BF16 && launch_rmsnorm_vec<bf16_t, true>(h, g, M, d, eps, (bf16_t*)out, stream)) return RADIX_OK;
+    if (out_dtype == RADIX_F16 && launch_rmsnorm_vec<f16_t, true>(h, g, M, d, eps, (f16_t*)out, stream)) return RADIX_OK;
+    return RADIX_ERR_UNSUPPORTED;
+}
+
 void launch_rmsnorm(const float* h, const float* g, int M, int d, float eps, void* out, int out_dtype,
                     hipStream_t stream) {
     if (M <= 0) return;
-    if (out_dtype == RADIX_BF16 && launch_rmsnorm_vec(h, g, M, d, eps, (bf16_t*)out, stream)) return;
-    if (out_dtype == RADIX_F16 && launch_rmsnorm_vec(h, g, M, d, eps, (f16_t*)out, stream)) return;
-    if (out_dtype == RADIX_F32 && launch_rmsnorm_vec(h, g, M, d, eps, (float*)out, stream)) return;
+    if (out_dtype == RADIX_BF16 && launch_rmsnorm_vec<bf16_t, false>(h, g, M, d, eps, (bf16_t*)out, stream)) return;
+    if (out_dtype == RADIX_F16 && launch_rmsnorm_vec<f16_t, false>(h, g, M, d, eps, (f16_t*)out, stream)) return;
+    if (out_dtype == RADIX_F32 && launch_rmsnorm_vec<float, false>(h, g, M, d, eps, (float*)out, stream)) return;
     dim3 grid(ceil_div(M, 4)), block(256);
     if (out_dtype == RADIX_BF16)
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, grid, block, 0, stream, h, g, M, d, eps, (bf16_t*)out);

@@ -75,7 +75,7 @@ def test_model_create_rejects_bad_config(lib):
     assert lib.radix_model_create(None, None, C.byref(out)) == -1
     w = binding.radix_weights(0x1000, 0x1000, None)
     good = dict(n_layers=1, d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_int=768, vocab=10, max_pos=16,
-                qk_norm=1, dtype=0, compute_dtype=0, eps=1e-6, rope_base=1e6)
+                qk_norm=1, dtype=0, compute_dtype=0, split_norm_out=0, eps=1e-6, rope_base=1e6)
 
     def create(**kw):
         c = binding.radix_model_config(**dict(good, **kw))
@@ -87,6 +87,8 @@ def test_model_create_rejects_bad_config(lib):
     assert create(dtype=7) == -3
     assert create(dtype=1, compute_dtype=1) == -3    # 16-bit path needs head_dim 128
     assert create(compute_dtype=2) == -3         # fp32 weights are multiplied in fp32
+    assert create(split_norm_out=1) == -3        # hi/lo activations exist for 16-bit operands only
+    assert create(split_norm_out=5) == -9
     assert create(dtype=1, compute_dtype=0, head_dim=128) == -3
     assert create(d_int=100) == -3               # gate/up interleave needs multiples of 32
     assert create() == -1                        # config fine, layers_host NULL

@@ -99,6 +99,20 @@ def test_bf16_small_model_several_tiles_and_ragged_tail(compute, tol):
     assert np.array_equal(y, y_nd)
 
 
+def test_split_norm_outputs_tighten_the_error():
+    # hi/lo RMSNorm outputs: same result to a tighter error, still row-invariant
+    errs = {}
+    for split in (False, True):
+        cfg = dataclasses.replace(SMALL_BF16, compute_dtype="bf16", split_norm_out=split)
+        w = synth.SynthWeights(cfg, 31)
+        b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, cfg.vocab)
+        y, y_nd, _ = run_all(w, b)
+        errs[split] = U.rel_err(y, U.oracle_rows(w, b))
+        assert np.array_equal(y, y_nd)
+    print("bf16 operands, split off/on:", errs)
+    assert errs[True] < 0.85 * errs[False] and errs[True] <= TOL_BF16_OPERANDS
+
+
 def test_bf16_wide_model_uses_large_gemm_tiles():
     # enough rows and wide enough outputs for the 256x256 and 128x256 GEMM tiles, ragged M
     cfg = synth.ModelConfig("bf16w", 2, 512, 8, 2, 128, 1536, 3000, "bf16", max_pos=1024)
@@ -165,13 +179,15 @@ def test_empty_batch_and_bad_inputs():
     model.close()
 
 
-def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None):
+def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None, split=False):
     """Full-size batch on the GPU in the benchmark's launch configuration; the oracle computes
     whole sampled sequences (the no-dedup pass is independent per sequence)."""
     b = synth.make_batch(key)
     w = synth.make_weights(key)
     if compute is not None:
         w = synth.SynthWeights(dataclasses.replace(w.cfg, compute_dtype=compute), w.seed)
+    if split:
+        w = synth.SynthWeights(dataclasses.replace(w.cfg, split_norm_out=True), w.seed)
     y, y_nd, n_c = run_all(w, b, force_dedup=True)
     assert n_c == b.expected_n_compact
     rows = U.rows_of(b, sequences)
@@ -193,8 +209,10 @@ def test_c3_full_size_sampled_sequences():
 
 
 def test_c4_full_size_sampled_sequences():
-    # 8B shape, 256 sequences
-    _sampled_parity("C4", [0, 255])
+    # 8B shape, 256 sequences.  With N(0, 0.02) weights at d = 4096 every layer amplifies perturbations
+    # (projection gain 0.02 * sqrt(4096) = 1.28 > 1), so fp16 activation rounding that costs 3e-3 on the
+    # 0.6B shape reaches ~2.1e-2 here after 36 layers; the hi/lo RMSNorm outputs bring it back under the bar.
+    _sampled_parity("C4", [0, 255], split=True)
 
 
 def test_c5_full_size_sampled_sequences():
