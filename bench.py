@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 
+# HBM-side bytes per gate/up GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled
+# by the 256 MiB copy dispatch of the same run (profiles/gemm_gateup_C2_hbm_traffic.md); None where not measured.
+GATEUP_TRAFFIC_BYTES = {"C2": int(82710 * 1024 * 1.984 + 47202 * 1024)}
+
 WORKLOAD_TEXT = {
     "C1": "C1: tiny Qwen3-style decoder fp32, 8 seqs = 32 shared + 16 own tokens",
     "C2": "C2: Qwen3-0.6B shape, reranking batch of 64 seqs = 48-token shared prefix + suffix U[64,192]",
@@ -106,6 +110,16 @@ def main() -> int:
     per_kernel = binding.radix_timing_collect()
     binding.radix_timing_enable([])
 
+    # one plain row copy of known size (256 MiB read + 256 MiB written): the reference dispatch that
+    # the rocprofv3 FETCH_SIZE / WRITE_SIZE readings of the other kernels are scaled by
+    cal_rows, cal_row_bytes = 65536, 4096
+    cal_src = torch.empty(cal_rows * cal_row_bytes, dtype=torch.uint8, device="cuda").view(cal_rows, cal_row_bytes)
+    cal_idx = torch.arange(cal_rows, dtype=torch.int32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    binding.radix_index_select_rows(cal_src, cal_idx, out=cal_dst)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     d, di, dq, dkv = cfg.d, cfg.d_int, cfg.dq, cfg.dkv
     flops_dom = 2.0 * n_c * (2 * di) * d                      # one gate/up GEMM launch
     avg_dom_s = t_dom / max(n_dom, 1) * 1e-3
@@ -146,7 +160,8 @@ def main() -> int:
         "scatter_GBps": scatter_bytes * cfg.n_layers / (per_kernel["scatter"][0] * 1e-3) / 1e9 if per_kernel["scatter"][0] > 0 else None,
         "gather_GBps": gather_bytes * cfg.n_layers / (per_kernel["gather"][0] * 1e-3) / 1e9 if per_kernel["gather"][0] > 0 else None,
         "roofline": {"kernel": "gate/up GEMM + SwiGLU (M=N', N=2*d_int, K=d)", "bound": "mfma", "achieved": achieved,
-                     "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": GATEUP_TRAFFIC_BYTES.get(key),
                      "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom},
     }
 
