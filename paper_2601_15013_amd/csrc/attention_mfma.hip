@@ -1,18 +1,25 @@
-// 16-bit (bf16 or fp16 operands) causal varlen GQA attention on the full ragged layout (head_dim = 128), MFMA + online
-// softmax.  (Paper: Algorithm 1, "FlashAttn(q, k, v, cu_seqlens, causal=True)"; "Integration
-// with Attention": attention is the only step that needs all N rows.)
+// 16-bit (bf16 or fp16 operands) causal varlen GQA attention on the full ragged layout (head_dim = 128),
+// MFMA + online softmax.  (Paper: Algorithm 1, "FlashAttn(q, k, v, cu_seqlens, causal=True)";
+// "Integration with Attention": attention is the only step that needs all N rows.)
 //
 // One workgroup = 4 wavefronts x 32 queries working on ONE KV head: HPB query heads of its GQA
 // group (HPB = min(group, 4)) times 128 / HPB query rows, so the K/V tile staged in LDS is shared
 // by the query heads of the group and short sequences waste fewer empty query rows.
-// Keys/values are walked in tiles of 64 staged in LDS; the next tile's global loads are issued
-// before the current tile is multiplied, so their latency overlaps the MFMAs.  Scores are produced TRANSPOSED,
-// S^T[key, query] = K * Q^T with v_mfma_f32_32x32x16_{bf16,f16}, so that a lane owns one query column:
-// row maxima and sums are in-lane reductions plus one exchange with lane ^ 32, and the running
-// rescale factor is a per-lane scalar.  The second product is O^T[hd, query] = V^T * P^T, whose
-// B operand is exactly the register layout S^T was produced in (the k index of an MFMA may be
-// permuted freely as long as both operands agree), and whose A operand needs V transposed:
-// V is transposed once per tile on its way into LDS.
+//
+// Data path.  K and V tiles of 64 keys go global -> LDS with global_load_lds_dwordx4 (no VGPR
+// staging), both row-major [key][128], two stages: the loads of tile t+1 are issued right after the
+// barrier that retires tile t-1 and land while tile t is multiplied; one barrier per tile.  The DMA
+// writes LDS linearly, so the XOR swizzles that keep the fragment reads bank-conflict free are
+// applied to the global address a lane fetches.
+//
+// Scores are produced TRANSPOSED, S^T[key, query] = K * Q^T with v_mfma_f32_32x32x16_{bf16,f16}, so
+// that a lane owns one query column: row maxima and sums are in-lane reductions plus one exchange
+// with lane ^ 32, and the running rescale factor is a per-lane scalar.  The second product is
+// O^T[hd, query] = V^T * P^T.  Its B operand is exactly the register layout S^T was produced in (the
+// k index of an MFMA may be permuted freely as long as both operands agree).  Its A operand needs,
+// per lane, 8 keys of one hd column out of the row-major V tile: that is what ds_read_b64_tr_b16
+// delivers - 16 lanes hand in the addresses of a 4-key x 16-column block (lane 4 e + a: key e, columns
+// 4 a .. 4 a + 3) and lane l receives column l of keys 0..3 - so V is never transposed in memory.
 #include "common.h"
 #include "kernels.h"
 
@@ -21,22 +28,47 @@ namespace {
 constexpr int HD = 128;
 constexpr int BKV = 64;     // keys per tile
 constexpr int ATT_THREADS = 256;
+constexpr int TILE_SLOTS = BKV * 16;    // 16-byte slots of one K or V tile (16 KB)
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+template <int N> __device__ __forceinline__ void att_wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+// Asynchronous 16-byte-per-lane copy global -> LDS: lane L of the wavefront writes LDS bytes
+// [lds_base + 16 L, +16); global address = uniform base + per-lane byte offset.
+__device__ __forceinline__ void att_dma16(const void* base, uint32_t lane_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ uint32_t att_lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
 
 template <int DT, int HPB>
 __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
-                                                                     const int32_t* __restrict__ cu, int N,
-                                                                     int n_q_heads, int n_kv_heads, int n_qtiles,
-                                                                     typename Op<DT>::T* __restrict__ out) {
+                                                                        const int32_t* __restrict__ cu, int N,
+                                                                        int n_q_heads, int n_kv_heads, int n_qtiles,
+                                                                        int n_pairs,
+                                                                        typename Op<DT>::T* __restrict__ out) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
-    __shared__ uint4 Ks[BKV * 16];          // [key][16 chunks of 8 hd], chunk ^= key & 15
-    __shared__ uint32_t Vt[HD * 32];        // [hd][32 words of 2 keys], 8-byte chunk ^= (hd >> 1) & 15
+    // [stage][key][16 chunks of 8 hd].  K: chunk ^= key & 15 (a fragment read walks 16 keys of one
+    // chunk column).  V: chunk ^= (key & 3) << 2 (a transpose read walks 4 keys of one 64-byte column block).
+    __shared__ uint4 Ks[2][TILE_SLOTS];
+    __shared__ uint4 Vs[2][TILE_SLOTS];
 
     constexpr int BQ = 128 / HPB;                       // query rows per workgroup
     constexpr int WPH = 4 / HPB;                        // wavefronts per query head
-    const int seq = blockIdx.z;
-    const int qt = n_qtiles - 1 - (int)blockIdx.x;      // heavy (late) tiles first
+    // Work item = (sequence, head group, query tile).  Workgroup ids are dealt round-robin to the 8
+    // XCDs, each with its own L2: id % 8 picks the XCD, and all query tiles of one (sequence, head
+    // group) - which walk the same K/V rows - are given to the same XCD, consecutively.
+    const int n_hg = n_q_heads / HPB;
+    const int pair = ((int)blockIdx.x / 8 / n_qtiles) * 8 + (int)blockIdx.x % 8;    // (sequence, head group)
+    if (pair >= n_pairs) return;
+    const int seq = pair / n_hg, hgroup = pair % n_hg;
+    const int qt = n_qtiles - 1 - ((int)blockIdx.x / 8) % n_qtiles;                  // heavy (late) tiles first
     // clamped so that a malformed cu_seqlens can never index outside the N rows
     int start = cu[seq], end = cu[seq + 1];
     start = start < 0 ? 0 : (start > N ? N : start);
@@ -45,16 +77,35 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     const int q0 = qt * BQ;
     if (q0 >= len) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, g = lane >> 5;
     const int group = n_q_heads / n_kv_heads;
-    const int h = (int)blockIdx.y * HPB + wave / WPH;   // query head of this wavefront
-    const int kvh = h / group;                          // same for all wavefronts: HPB divides group
+    const int h = hgroup * HPB + wave / WPH;            // query head of this wavefront
+    const int kvh = (hgroup * HPB) / group;             // one KV head per workgroup: HPB divides group
     const int wq = wave % WPH;                          // 32-row slice of the query tile
     const int dq = n_q_heads * HD, dkv = n_kv_heads * HD;
     const size_t row = (size_t)dq + 2 * (size_t)dkv;
-    const T* kbase = qkv + (size_t)start * row + dq + (size_t)kvh * HD;
-    const T* vbase = kbase + dkv;
+    const uint32_t row_bytes = (uint32_t)(row * sizeof(T));
+    const char* kbase = (const char*)(qkv + (size_t)start * row + dq + (size_t)kvh * HD);
+    const char* vbase = kbase + (size_t)dkv * sizeof(T);
+
+    // ---- K/V tile loads: wavefront w fills tile rows [16 w, 16 w + 16) of K and of V, 4 rows (1 KB) per
+    // instruction: lane L -> row 4 j + L / 16, LDS chunk L % 16, global chunk = LDS chunk ^ swizzle(row).
+    // Rows past the end of the sequence are clamped (the causal mask hides them).
+    const int lrow = lane >> 4, lpc = lane & 15;
+    auto issue_tile = [&](int kv0, int stage) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = 16 * wave + 4 * j + lrow;             // tile row = key
+            int kr = kv0 + r;
+            kr = kr < len ? kr : len - 1;
+            const uint32_t rb = (uint32_t)kr * row_bytes;
+            att_dma16(kbase, rb + 16u * (uint32_t)(lpc ^ (r & 15)), att_lds_addr(&Ks[stage][(16 * wave + 4 * j) * 16]));
+            att_dma16(vbase, rb + 16u * (uint32_t)(lpc ^ ((r & 3) << 2)), att_lds_addr(&Vs[stage][(16 * wave + 4 * j) * 16]));
+        }
+    };
+    issue_tile(0, 0);
 
     // ---- Q fragment (B operand of S^T = K Q^T): lane (n, g) holds Q[query n][16 ks + 8 g .. +8]
     const int qi = q0 + wq * 32 + n;                    // query offset inside the sequence
@@ -75,124 +126,118 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[b][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
-    const float sc = 1.4426950408889634f / sqrtf((float)HD);     // log2(e) / sqrt(hd)
+    const float sc = 1.4426950408889634f / sqrtf((float)HD);     // log2(e) / sqrt(hd), applied inside the exponent
 
     const int wave_qmin = q0 + wq * 32, wave_qmax = wave_qmin + 31;
     const int last_q = (q0 + BQ - 1) < (len - 1) ? (q0 + BQ - 1) : (len - 1);
     const int n_tiles = last_q / BKV + 1;
 
-    // global -> register loads of one K/V tile (rows past the end of the sequence are clamped; the
-    // causal mask hides them).  K: thread -> chunk tid % 16 of keys tid / 16 + 16 i.  V: lane -> key
-    // pair n, 8 hd columns c8 = wave * 4 + i * 2 + g, so that the transposed store packs 2 keys a word.
-    uint4 rk[4], rva[2], rvb[2];
-    auto load_tile = [&](int kv0) {
-        const int c = tid & 15;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int kr = kv0 + (tid >> 4) + 16 * i;
-            kr = kr < len ? kr : len - 1;
-            rk[i] = *((const uint4*)(kbase + (size_t)kr * row) + c);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int c8 = wave * 4 + i * 2 + g;
-            int k0r = kv0 + 2 * n, k1r = k0r + 1;
-            k0r = k0r < len ? k0r : len - 1;
-            k1r = k1r < len ? k1r : len - 1;
-            rva[i] = *((const uint4*)(vbase + (size_t)k0r * row) + c8);
-            rvb[i] = *((const uint4*)(vbase + (size_t)k1r * row) + c8);
-        }
-    };
-    load_tile(0);
+    // transpose-read addressing of V (see the header): 16-lane group = lane / 16 -> g = group / 2,
+    // 16-column half = group % 2; inside the group lane i = 4 e + a reads key e, columns 4 a .. 4 a + 3.
+    const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_half = (lane >> 4) & 1;
+    // byte offset inside a V tile of (key 4 g + tr_e [+ 16 kk + 8 second], columns 32 b + 16 half + 4 a):
+    //   key * 256 + ((chunk ^ (tr_e << 2)) << 4) + (a & 1) * 8   with chunk = 4 b + 2 half + a / 2
+    const uint32_t tr_key0 = (uint32_t)(4 * g + tr_e) * 256u + (uint32_t)(tr_a & 1) * 8u;
+    const int tr_chunk0 = 2 * tr_half + (tr_a >> 1);
 
     for (int t = 0; t < n_tiles; ++t) {
         const int kv0 = t * BKV;
-        __syncthreads();
-        // ---- K tile -> LDS (row-major, swizzled); V tile -> LDS transposed
-        {
-            const int c = tid & 15;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int key = (tid >> 4) + 16 * i;
-                Ks[key * 16 + (c ^ (key & 15))] = rk[i];
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int c8 = wave * 4 + i * 2 + g;
-                const uint32_t aw[4] = {rva[i].x, rva[i].y, rva[i].z, rva[i].w};
-                const uint32_t bw[4] = {rvb[i].x, rvb[i].y, rvb[i].z, rvb[i].w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t lo = (aw[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-                    const uint32_t hi = (bw[e >> 1] >> ((e & 1) * 16)) & 0xFFFFu;
-                    const int hd = c8 * 8 + e;
-                    Vt[hd * 32 + (((n >> 1) ^ ((hd >> 1) & 15)) << 1) + (n & 1)] = lo | (hi << 16);
-                }
-            }
-        }
-        __syncthreads();
-        if (t + 1 < n_tiles) load_tile(kv0 + BKV);     // in flight while this tile is multiplied
-        if (kv0 > wave_qmax) continue;          // whole tile is in this wavefront's future
+        const int st = t & 1;
+        att_wait_vmcnt<0>();                // this wavefront's share of tile t has landed
+        __syncthreads();                    // everybody's has; everybody is done with tile t-1
+        if (t + 1 < n_tiles) issue_tile(kv0 + BKV, st ^ 1);
+        if (kv0 > wave_qmax) continue;      // whole tile is in this wavefront's future
 
-        // ---- S^T = K Q^T : two 32-key blocks
+        // ---- S^T = K Q^T : two 32-key blocks x 8 k-steps.  The K fragments are read from LDS four MFMAs
+        // ahead of their use (the scheduling barriers pin that order), so LDS latency hides behind the
+        // matrix pipe.  MFMA t: key block t & 1, k-step t >> 1.
         f32x16 s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
-            const int key = kb * 32 + n;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                uint4 v = Ks[key * 16 + ((ks * 2 + g) ^ (key & 15))];
-                s[kb] = Op<DT>::mfma(*reinterpret_cast<V8*>(&v), qf[ks], s[kb]);
-            }
-        }
-        // ---- scale, causal mask (register e of block kb is key kv0 + 32 kb + 8 (e/4) + 4 g + e%4)
-        const bool need_mask = (kv0 + BKV - 1) > wave_qmin;
-        float tmax = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float v = s[kb][e] * sc;
-                if (need_mask) {
-                    const int kj = kv0 + kb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
-                    if (kj > qi_c) v = -INFINITY;
-                }
-                s[kb][e] = v;
-                tmax = fmaxf(tmax, v);
+            for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
+        {
+            uint4 kf[16];
+            auto read_k = [&](int u) {
+                const int key = (u & 1) * 32 + n;
+                kf[u] = Ks[st][key * 16 + (((u >> 1) * 2 + g) ^ (key & 15))];
+            };
+#pragma unroll
+            for (int u = 0; u < 4; ++u) read_k(u);
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (u + 4 < 16) read_k(u + 4 < 16 ? u + 4 : 0);
+                s[u & 1] = Op<DT>::mfma(*reinterpret_cast<V8*>(&kf[u]), qf[u >> 1], s[u & 1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+        // V^T fragments of the second product, MFMA u: k-step u >> 2 (16 keys), hd block u & 3.  The first
+        // four are requested now and arrive during the softmax.
+        const char* vt = (const char*)&Vs[st][0];
+        s16x4 vlo[16], vhi[16];
+        auto read_v = [&](int u) {
+            const int kk = u >> 2, b = u & 3;
+            const uint32_t off = tr_key0 + (uint32_t)kk * 4096u + (uint32_t)(((4 * b + tr_chunk0) ^ (tr_e << 2)) << 4);
+            vlo[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vt + off));
+            vhi[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vt + off + 2048u));
+        };
+#pragma unroll
+        for (int u = 0; u < 4; ++u) read_v(u);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // ---- causal mask on diagonal tiles (register e of block kb is key kv0 + 32 kb + 8 (e/4) + 4 g + e%4),
+        // running maximum of the raw scores, p = 2^(s c - m c) with one fma + one v_exp per element
+        if ((kv0 + BKV - 1) > wave_qmin) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int kj = kv0 + kb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+                    if (kj > qi_c) s[kb][e] = -INFINITY;
+                }
+        }
+        float tmax = s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, s[kb][e]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
         const float m_new = fmaxf(m_run, tmax);       // finite: tile 0 always holds key 0 <= query
-        const float alpha = exp2f(m_run - m_new);
-        m_run = m_new;
+        const float neg_mc = -m_new * sc;
         float psum = 0.f;
         V8 pf[4];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(s[kb][e] - m_new);
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[kb][e], sc, neg_mc));
                 psum += p;
                 pf[kb * 2 + (e >> 3)][e & 7] = (T)p;
             }
-        l_run = l_run * alpha + psum;
+        // rescale the running sums only when some query of the wavefront saw a new maximum
+        if (__any(m_new != m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);     // 0 on the first tile (m_run = -inf)
+            l_run *= alpha;
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+                for (int e = 0; e < 16; ++e) o[b][e] *= alpha;
+        }
+        l_run += psum;
+        m_run = m_new;
 
-        // ---- O^T += V^T P^T : 4 hd blocks x 4 k-steps of 16 keys
+        // ---- O^T += V^T P^T : 4 k-steps of 16 keys x 4 hd blocks, V^T fragments read four MFMAs ahead.
+        // Key order inside a k-step: the lo read holds keys 16 kk + 4 g + 0..3, the hi read 16 kk + 8 + 4 g + 0..3,
+        // which is the order the P^T registers of k-step kk are in.
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int hd = b * 32 + n;
-                const uint2 lo = *reinterpret_cast<const uint2*>(&Vt[hd * 32 + (((4 * kk + g) ^ ((hd >> 1) & 15)) << 1)]);
-                const uint2 hi = *reinterpret_cast<const uint2*>(&Vt[hd * 32 + (((4 * kk + 2 + g) ^ ((hd >> 1) & 15)) << 1)]);
-                uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-                o[b] = Op<DT>::mfma(*reinterpret_cast<V8*>(&v), pf[kk], o[b]);
-            }
+        for (int u = 0; u < 16; ++u) {
+            if (u + 4 < 16) read_v(u + 4 < 16 ? u + 4 : 0);
+            union { struct { s16x4 lo, hi; } p; V8 v; } cvt;
+            cvt.p.lo = vlo[u];
+            cvt.p.hi = vhi[u];
+            o[u & 3] = Op<DT>::mfma(cvt.v, pf[u >> 2], o[u & 3]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -220,15 +265,20 @@ int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int 
     if (N <= 0 || B <= 0) return RADIX_OK;
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
     if (max_seqlen <= 0) return RADIX_ERR_BAD_SIZE;
-    if (B > 65535 || n_q_heads > 65535) return RADIX_ERR_UNSUPPORTED;
     if (op_dtype != RADIX_BF16 && op_dtype != RADIX_F16) return RADIX_ERR_UNSUPPORTED;
+    if ((((uintptr_t)qkv | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
     const int group = n_q_heads / n_kv_heads;
     const int hpb = (group % 4 == 0) ? 4 : (group % 2 == 0 ? 2 : 1);    // query heads per workgroup
     const int n_qtiles = ceil_div(max_seqlen, 128 / hpb);
-    const dim3 grid(n_qtiles, n_q_heads / hpb, B), block(ATT_THREADS);
+    const int n_pairs = (n_q_heads / hpb) * B;
+    const long long n_blocks = (long long)ceil_div(n_pairs, 8) * 8 * n_qtiles;
+    if (n_blocks > 0x7FFFFFFFLL) return RADIX_ERR_UNSUPPORTED;
+    // per-lane 32-bit byte offsets inside one sequence's K/V rows
+    if ((long long)max_seqlen * (n_q_heads + 2 * n_kv_heads) * HD * 2 >= (1LL << 32)) return RADIX_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)n_blocks), block(ATT_THREADS);
 #define RADIX_ATT(DT, HPB)                                                                                       \
     hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,   \
-                       n_q_heads, n_kv_heads, n_qtiles, (Op<DT>::T*)out)
+                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out)
     if (op_dtype == RADIX_BF16) {
         if (hpb == 4) RADIX_ATT(RADIX_BF16, 4); else if (hpb == 2) RADIX_ATT(RADIX_BF16, 2); else RADIX_ATT(RADIX_BF16, 1);
     } else {
