@@ -197,8 +197,9 @@ int radix_device_status(void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Optional per-kernel timing for benchmarks.  While a category's bit is set in category_mask,
- * the forward calls bracket every launch of that category with a pair of HIP events recorded on
- * the caller's stream.  radix_timing_collect waits for the device, writes for every category the
+ * the forward calls bracket every every_nth-th launch of that category (0 or 1: every launch) with a
+ * pair of HIP events recorded on the caller's stream; an event pair costs a few microseconds of idle
+ * GPU around the launch it brackets, so timing inside a timed region should sample sparsely.  radix_timing_collect waits for the device, writes for every category the
  * summed elapsed milliseconds and the number of timed launches since the last collect/enable
  * (arrays of RADIX_TIMING_CATEGORIES entries, HOST pointers) and resets the counters.
  * Process-wide state, not thread-safe; meant for one benchmarking thread.  Mask 0 disables.
@@ -214,7 +215,7 @@ enum {
     RADIX_TIME_ROWOPS = 7,
     RADIX_TIMING_CATEGORIES = 8
 };
-int radix_timing_enable(uint32_t category_mask);
+int radix_timing_enable(uint32_t category_mask, uint32_t every_nth);
 int radix_timing_collect(float* total_ms_host, int32_t* launches_host);
 
 /* Static description of a radix_status value. */

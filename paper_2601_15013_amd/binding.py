@@ -74,7 +74,7 @@ def _lib() -> C.CDLL:
         lib.radix_prefill_forward_nodedup.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
         lib.radix_index_select_rows.argtypes = [vp, i32, vp, i32, sz, vp, vp, vp]
         lib.radix_device_status.argtypes = [vp, sz, vp]
-        lib.radix_timing_enable.argtypes = [C.c_uint32]
+        lib.radix_timing_enable.argtypes = [C.c_uint32, C.c_uint32]
         lib.radix_timing_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
         lib.radix_status_string.argtypes = [C.c_int]
         lib.radix_status_string.restype = C.c_char_p
@@ -237,11 +237,11 @@ def radix_device_status(ws: torch.Tensor, stream: Optional[torch.cuda.Stream] = 
     return _lib().radix_device_status(_ptr(ws), ws.numel(), _stream(stream))
 
 
-def radix_timing_enable(categories: Sequence[str]) -> None:
+def radix_timing_enable(categories: Sequence[str], every_nth: int = 1) -> None:
     mask = 0
     for c in categories:
         mask |= 1 << TIMING_CATEGORIES.index(c)
-    _check(_lib().radix_timing_enable(mask), "radix_timing_enable")
+    _check(_lib().radix_timing_enable(mask, every_nth), "radix_timing_enable")
 
 
 def radix_timing_collect() -> dict:

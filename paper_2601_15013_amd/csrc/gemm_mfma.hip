@@ -140,6 +140,18 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 
     const int KT = K / BK;
 
+    // EPI_QKV_ROPE: position ids of this lane's rows, fetched before the main loop so that the RoPE
+    // table rows can be addressed without a dependent load when the epilogue starts
+    int rope_pos[MB];
+    if (EPI == EPI_QKV_ROPE) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            int gm = m0 + wm * WTM + i * 32 + r;
+            gm = gm < M ? gm : M - 1;
+            rope_pos[i] = qe.pos_c[gm];
+        }
+    }
+
     // fragment f of a k-step: f < MB is an activation fragment, else a weight fragment
 #define RADIX_FRAG1(ST, KS, FA, FB, F)                                                                             \
     do {                                                                                                           \
@@ -302,8 +314,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                     // column c + 64 (block j + 2) of the same lane and register.  (Paper: Q/K norms and
                     // RoPE are position-wise, hence run on compact rows - "Integration with Attention".)
                     const int i = ip + il;
-                    int gm = m0 + wm * WTM + i * 32 + r;
-                    gm = gm < M ? gm : M - 1;
                     float rs = 1.0f;
                     if (qe.qk_norm) {
                         float ss = 0.f;
@@ -314,9 +324,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                         ss += __shfl_xor(ss, 32, 64);
                         rs = 1.0f / sqrtf(ss * (1.0f / 128.0f) + qe.eps);
                     }
-                    const int p = qe.pos_c[gm];
-                    const float* ct = qe.cos_tab + (size_t)p * 64;
-                    const float* st = qe.sin_tab + (size_t)p * 64;
+                    const float* ct = qe.cos_tab + (size_t)rope_pos[i] * 64;
+                    const float* st = qe.sin_tab + (size_t)rope_pos[i] * 64;
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
 #pragma unroll

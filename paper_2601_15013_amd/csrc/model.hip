@@ -31,10 +31,13 @@ namespace {
 // to measure a kernel's average launch duration inside the timed region)
 struct KernelTimer {
     uint32_t mask = 0;
+    uint32_t stride = 1;                                   // bracket every stride-th launch of a category
+    size_t seen[RADIX_TIMING_CATEGORIES] = {};
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool[RADIX_TIMING_CATEGORIES];
     size_t used[RADIX_TIMING_CATEGORIES] = {};
     int begin(int cat, hipStream_t s) {
         if (!(mask >> cat & 1u)) return -1;
+        if (seen[cat]++ % stride != 0) return -1;
         if (used[cat] == pool[cat].size()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return -1;
@@ -408,9 +411,10 @@ extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int
                         (hipStream_t)stream);
 }
 
-extern "C" int radix_timing_enable(uint32_t category_mask) {
+extern "C" int radix_timing_enable(uint32_t category_mask, uint32_t every_nth) {
     g_timer.mask = category_mask & ((1u << RADIX_TIMING_CATEGORIES) - 1u);
-    for (int c = 0; c < RADIX_TIMING_CATEGORIES; ++c) g_timer.used[c] = 0;
+    g_timer.stride = every_nth ? every_nth : 1;
+    for (int c = 0; c < RADIX_TIMING_CATEGORIES; ++c) g_timer.used[c] = g_timer.seen[c] = 0;
     return RADIX_OK;
 }
 
