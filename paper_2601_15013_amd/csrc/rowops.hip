@@ -24,7 +24,16 @@ __global__ __launch_bounds__(256) void index_select_kernel(const V* __restrict__
     }
     const V* sp = src + (size_t)s * row_vecs;
     V* dp = dst + (size_t)row * row_vecs;
-    for (int c = lane; c < row_vecs; c += 64) dp[c] = sp[c];
+    // 8 accesses in flight per lane: all loads of a 512-vector chunk are issued before its stores
+    int c = lane;
+    for (; c + 7 * 64 < row_vecs; c += 8 * 64) {
+        V v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = sp[c + 64 * k];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dp[c + 64 * k] = v[k];
+    }
+    for (; c < row_vecs; c += 64) dp[c] = sp[c];
 }
 
 // cu_seqlens must run from 0 to N without decreasing and no sequence may exceed max_seqlen.
