@@ -77,16 +77,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
     static_assert(EPI != EPI_SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
     static_assert(EPI != EPI_QKV_ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
-    static_assert(LOADS * 3 < 64, "vmcnt range");
+    static_assert(LOADS * 4 < 64, "vmcnt range");
 
     constexpr int EPI_PITCH = 272;                             // epilogue row pitch in bytes (256 + 16 pad)
     constexpr int EPI_SLOTS = 4 * 64 * EPI_PITCH / 16;         // 4 wavefronts x 64 rows
-    constexpr int LDS_SLOTS = 4 * STAGE > EPI_SLOTS ? 4 * STAGE : EPI_SLOTS;
+    constexpr int LDS_SLOTS = 5 * STAGE > EPI_SLOTS ? 5 * STAGE : EPI_SLOTS;
     __shared__ uint4 lds_all[LDS_SLOTS];
-    uint4* const st0 = lds_all;
-    uint4* const st1 = lds_all + STAGE;
-    uint4* const st2 = lds_all + 2 * STAGE;
-    uint4* const st3 = lds_all + 3 * STAGE;
 
     // ---- tile assignment: XCD-aware renumbering, then row-tile bands of 8 sweeping the columns
     int pid = blockIdx.x;
@@ -152,34 +148,53 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         }
     }
 
+    // ---- LDS addressing.  The ring has five stages of STAGE_B bytes; tile t lives in stage t % 5.
+    // Stage byte offsets are wave-uniform scalars that rotate as the loop advances, everything
+    // lane-dependent is computed once: per k-step ks the byte offset of this lane's chunk in tile row
+    // (wave row block) + r; fragment f of the block adds f * 32 rows = f * 2048 bytes.
+    constexpr uint32_t STAGE_B = STAGE * 16;
+    const char* const lds_c = (const char*)lds_all;
+    const uint32_t lds_base = lds_addr(lds_all);
+    uint32_t a_rd[2], b_rd[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        a_rd[ks] = (uint32_t)slot(wm * WTM + r, ks * 2 + g) * 16;
+        b_rd[ks] = (uint32_t)(BM * 4 + slot(wn * WTN + r, ks * 2 + g)) * 16;
+    }
+
     // fragment f of a k-step: f < MB is an activation fragment, else a weight fragment
-#define RADIX_FRAG1(ST, KS, FA, FB, F)                                                                             \
+#define RADIX_FRAG1(SO, KS, FA, FB, F)                                                                             \
     do {                                                                                                           \
-        const int ch = (KS) * 2 + g;                                                                               \
         if ((F) < MB) {                                                                                            \
-            uint4 v = (ST)[slot(wm * WTM + (F) * 32 + r, ch)];                                                     \
+            uint4 v = *reinterpret_cast<const uint4*>(lds_c + (SO) + a_rd[KS] + (F) * 2048);                       \
             FA[(F) < MB ? (F) : 0] = *reinterpret_cast<V8*>(&v);                                                   \
         } else {                                                                                                   \
-            uint4 v = (ST)[BM * 4 + slot(wn * WTN + ((F) - MB) * 32 + r, ch)];                                     \
+            uint4 v = *reinterpret_cast<const uint4*>(lds_c + (SO) + b_rd[KS] + ((F) - MB) * 2048);                \
             FB[(F) >= MB ? (F) - MB : 0] = *reinterpret_cast<V8*>(&v);                                             \
         }                                                                                                          \
     } while (0)
 
-#define RADIX_DMA1(KT_, ST, F)                                                                                     \
+#define RADIX_DMA1(KT_, SO, F)                                                                                     \
     do {                                                                                                           \
         if ((F) < A_LOADS)                                                                                         \
             dma16(a_base + (size_t)(KT_) * (BK * sizeof(T)), a_off[(F) < A_LOADS ? (F) : 0],                       \
-                  lds_addr((ST) + 64 * (wave + 4 * (F))));                                                         \
+                  lds_base + (SO) + 1024 * (wave + 4 * (F)));                                                      \
         else if ((F) < LOADS)                                                                                      \
             dma16(w_base + (size_t)((KT_) >= WKT ? (KT_) - WKT : (KT_)) * (BK * sizeof(T)),                        \
                   w_off[(F) >= A_LOADS && (F) < LOADS ? (F) - A_LOADS : 0],                                        \
-                  lds_addr((ST) + BM * 4 + 64 * (wave + 4 * ((F) - A_LOADS))));                                    \
+                  lds_base + (SO) + BM * 64 + 1024 * (wave + 4 * ((F) - A_LOADS)));                                \
     } while (0)
 
-#define RADIX_ISSUE(TILE, ST)                                                                                      \
+    // loads of k-tiles T0 and T0+1, row group by row group: the two 64-byte halves of every 128-byte
+    // line are requested back to back, so the second request merges with the first one's miss in the
+    // vector L1 and the line crosses the L2 fabric once (requested a k-tile apart it crosses twice)
+#define RADIX_ISSUE2(T0, SA, SB)                                                                                   \
     do {                                                                                                           \
-        const int kt__ = (TILE) < KT ? (TILE) : KT - 1;                                                            \
-        _Pragma("unroll") for (int f = 0; f < LOADS; ++f) RADIX_DMA1(kt__, ST, f);                                 \
+        const int ka__ = (T0) < KT ? (T0) : KT - 2;                                                                \
+        _Pragma("unroll") for (int f = 0; f < LOADS; ++f) {                                                        \
+            RADIX_DMA1(ka__, SA, f);                                                                               \
+            RADIX_DMA1(ka__ + 1, SB, f);                                                                           \
+        }                                                                                                          \
     } while (0)
 
     // MFMAs [lo, hi) of the MB x NB block products of one k-step, in (j, i) order
@@ -189,59 +204,74 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
             acc[t / MB][t % MB] = Op<DT>::mfma(FB[t / MB], FA[t % MB], acc[t / MB][t % MB]);                       \
     } while (0)
 
-    // One k-tile = two k-steps of 16, software-pipelined over two fragment register sets and
-    // scheduled by hand (the scheduling barriers pin the order): the first half of a k-step's MFMAs
-    // is cut into UNITS slices, each led by one LDS fragment read for the NEXT k-step (and, in the
-    // second k-step, one global->LDS load of the tile three ahead); the second half of the MFMAs then
-    // covers the LDS latency of those reads, so the matrix pipe always has queued work.
-    // Between the two k-steps of tile kt+O: wait for this wavefront's share of tile kt+O+1, barrier
-    // (everybody's share has landed and everybody is past tile kt+O-1), then refill the stage tile
-    // kt+O-1 occupied with tile kt+O+3.  Tiles past the end are re-fetches of the last tile into a
-    // stage nobody reads again, which keeps the load-counter bookkeeping uniform.
-#define RADIX_STEP(CUR, NXT, REFILL, O)                                                            \
-    if (kt + (O) < KT) {                                                                           \
+    // first k-step of the tile in stage CUR: its MFMAs, led by the fragment reads of its second k-step
+#define RADIX_HALF0(CUR)                                                                           \
         _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                        \
             RADIX_FRAG1(CUR, 1, fa1, fb1, u);                                                      \
             RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);                  \
             __builtin_amdgcn_sched_barrier(0);                                                     \
         }                                                                                          \
         RADIX_MFMA_RANGE(fa0, fb0, HALF, MB * NB);                                                 \
-        __builtin_amdgcn_sched_barrier(0);                                                         \
-        wait_vmcnt<LOADS>();                                                                       \
-        __builtin_amdgcn_s_barrier();                                                              \
-        {                                                                                          \
-            const int kt__ = kt + (O) + 3 < KT ? kt + (O) + 3 : KT - 1;                            \
-            _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                    \
-                RADIX_DMA1(kt__, REFILL, u);                                                       \
-                RADIX_FRAG1(NXT, 0, fa0, fb0, u);                                                  \
-                RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);              \
-                __builtin_amdgcn_sched_barrier(0);                                                 \
-            }                                                                                      \
-            RADIX_MFMA_RANGE(fa1, fb1, HALF, MB * NB);                                             \
-            __builtin_amdgcn_sched_barrier(0);                                                     \
-        }                                                                                          \
-    }
+        __builtin_amdgcn_sched_barrier(0);
 
     constexpr int UNITS = MB + NB;
     constexpr int HALF = MB * NB / 2;      // the reads ride on the first half of a k-step's MFMAs
-    static_assert(UNITS >= LOADS, "one global->LDS load per slice");
+    static_assert(UNITS >= LOADS, "one pair of global->LDS loads per slice");
     V8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
-    RADIX_ISSUE(0, st0);
-    RADIX_ISSUE(1, st1);
-    RADIX_ISSUE(2, st2);
+    RADIX_ISSUE2(0, 0u, STAGE_B);
+    RADIX_ISSUE2(2, 2 * STAGE_B, 3 * STAGE_B);     // K = 64: tiles 0, 1 again, into stages nobody reads
     wait_vmcnt<LOADS * 2>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(st0, 0, fa0, fb0, u);
-    for (int kt = 0; kt < KT; kt += 4) {
-        RADIX_STEP(st0, st1, st3, 0)
-        RADIX_STEP(st1, st2, st0, 1)
-        RADIX_STEP(st2, st3, st1, 2)
-        RADIX_STEP(st3, st0, st2, 3)
+    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
+
+    // One k-tile = two k-steps of 16, software-pipelined over two fragment register sets and
+    // scheduled by hand (the scheduling barriers pin the order): the first half of a k-step's MFMAs
+    // is cut into UNITS slices, each led by one LDS fragment read for the NEXT k-step; the second half
+    // of the MFMAs then covers the LDS latency of those reads, so the matrix pipe always has queued work.
+    // K-tiles travel in PAIRS (t even, t+1).  The even tile needs neither wait nor barrier: its
+    // successor landed with the previous pair's barrier.  Between the two k-steps of the odd tile: wait
+    // for this wavefront's loads of the pair (t+2, t+3), barrier (everybody's share has landed and
+    // everybody is past tile t), then refill the stages of tiles t-1 and t with the pair (t+4, t+5),
+    // two loads per slice.  Pairs past the end re-fetch the last pair into those two stages, which
+    // nobody reads again: the loop body has no branch.
+    uint32_t so_e = 0, so_o = STAGE_B, so_n = 2 * STAGE_B, so_ra = 4 * STAGE_B;   // stages of t, t+1, t+2, t+4
+    for (int kt = 0; kt < KT; kt += 2) {
+        RADIX_HALF0(so_e)
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            RADIX_FRAG1(so_o, 0, fa0, fb0, u);
+            RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        RADIX_MFMA_RANGE(fa1, fb1, HALF, MB * NB);
+        __builtin_amdgcn_sched_barrier(0);
+
+        RADIX_HALF0(so_o)
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        const int ka = kt + 4 < KT ? kt + 4 : KT - 2;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            RADIX_DMA1(ka, so_ra, u);
+            RADIX_DMA1(ka + 1, so_e, u);           // tile t+5 goes where tile t was
+            RADIX_FRAG1(so_n, 0, fa0, fb0, u);
+            RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        RADIX_MFMA_RANGE(fa1, fb1, HALF, MB * NB);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // rotate by two stages: t+2 -> t
+        so_e = so_n;
+        so_o = so_n + STAGE_B == 5 * STAGE_B ? 0u : so_n + STAGE_B;
+        so_n = so_o + STAGE_B == 5 * STAGE_B ? 0u : so_o + STAGE_B;
+        so_ra = so_n + STAGE_B == 5 * STAGE_B ? 0u : so_n + STAGE_B;
+        so_ra = so_ra + STAGE_B == 5 * STAGE_B ? 0u : so_ra + STAGE_B;
     }
-#undef RADIX_STEP
+#undef RADIX_HALF0
+#undef RADIX_ISSUE2
 #undef RADIX_MFMA_RANGE
-#undef RADIX_ISSUE
 #undef RADIX_DMA1
 #undef RADIX_FRAG1
     wait_vmcnt<0>();                  // drain the tail loads ...
@@ -255,6 +285,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int PITCH = EPI_PITCH;
     char* const ebuf = (char*)lds_all + wave * (64 * PITCH);
     static_assert(MB % 2 == 0 && NB % 2 == 0, "passes of 64 rows / 64 columns");
+
+    // The epilogue derives all its addresses from a lane id the compiler cannot see through, so that
+    // none of that arithmetic is hoisted above the main loop, where every vector register counts.
+    int lane_opaque = lane;
+    asm volatile("" : "+v"(lane_opaque));
+    {
+    const int lane = lane_opaque;
+    const int r = lane & 31, g = lane >> 5;
 
     if (EPI == EPI_RESIDUAL) {
         // fp32 read-modify-write of the residual stream straight from the accumulator layout: per
@@ -371,13 +409,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
             }
         }
     }
+    }
 }
 
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
 int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out,
                const QkvEpilogue& qe, hipStream_t stream) {
     typedef typename Op<DT>::T T;
-    if (Nout % BN != 0 || K % BK != 0) return RADIX_ERR_UNSUPPORTED;
+    if (Nout % BN != 0 || K % (2 * BK) != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
     dim3 grid((unsigned)(tiles_m * tiles_n)), block(GEMM_THREADS);
 #define RADIX_LAUNCH(E)                                                                                       \
@@ -420,7 +459,7 @@ int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int e
     if (M <= 0 || Nout <= 0) return RADIX_OK;
     if (K <= 0) return RADIX_ERR_UNSUPPORTED;
     if (w_k == 0) w_k = K;
-    if (w_k != K && (2 * w_k != K || w_k % 32 != 0)) return RADIX_ERR_UNSUPPORTED;
+    if (w_k != K && (2 * w_k != K || w_k % (2 * BK) != 0)) return RADIX_ERR_UNSUPPORTED;
     if ((((uintptr_t)A | (uintptr_t)W | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
     QkvEpilogue qe = {};
     if (epilogue == EPI_QKV_ROPE) {
