@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--fused-attention", action="store_true",
+                    help="time the mode with scatter/gather folded into the attention kernel (default: the "
+                         "three-kernel scatter -> attention -> gather path of Algorithm 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough budget of the oracle timing")
     args = ap.parse_args()
@@ -72,10 +75,12 @@ def main() -> int:
     n_dev = torch.empty(1, dtype=torch.int32, device="cuda")
     force = key == "C5ctl"
 
-    def step():
+    fused = args.fused_attention
+
+    def step(fused_attention=fused):
         maps = binding.radix_build_index(tok, None, cu, run.ws, I_s, I_g, n_dev)
         binding.radix_prefill_forward(model, tok, None, cu, max_len, maps[0], maps[1], maps[3], run.ws, out=out,
-                                      force_dedup=force)
+                                      force_dedup=force, fused_attention=fused_attention)
         return maps[3]
 
     def timed(fn, iters):
@@ -103,11 +108,20 @@ def main() -> int:
     k2 = max(3, min(args.steps, 10))
     t_build = timed(lambda: binding.radix_build_index(tok, None, cu, run.ws, I_s, I_g, n_dev), k2)
     t_fwd = timed(lambda: binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out,
-                                                        force_dedup=force), k2)
+                                                        force_dedup=force, fused_attention=fused), k2)
+    # the other attention mode, for context: whole step and forward alone
+    t_step_other = timed(lambda: step(not fused), k2)
+    t_fwd_other = timed(lambda: binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws,
+                                                              out=out, force_dedup=force, fused_attention=not fused), k2)
     t_nodedup = timed(lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, max_len, run.ws, out=out), k2)
     binding.radix_timing_enable(binding.TIMING_CATEGORIES)
-    binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out, force_dedup=force)
+    binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out, force_dedup=force,
+                                  fused_attention=fused)
     per_kernel = binding.radix_timing_collect()
+    binding.radix_timing_enable(["attention"])
+    binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out, force_dedup=force,
+                                  fused_attention=not fused)
+    attn_other_ms = binding.radix_timing_collect()["attention"][0]
     binding.radix_timing_enable([])
 
     # one plain row copy of known size (256 MiB read + 256 MiB written): the reference dispatch that
@@ -148,11 +162,17 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[key], "B": B, "N": N, "N_compact": n_c,
                    "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": synth.WORKLOADS[key].seed,
-                   "weights": cfg.dtype, "operands": cfg.compute_dtype, "accumulate": "f32"},
+                   "weights": cfg.dtype, "operands": cfg.compute_dtype, "accumulate": "f32",
+                   "attention_mode": "fused (indexed q/k/v, representative rows only)" if fused
+                   else "scatter -> attention over N rows -> gather"},
         "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
         "speedup_vs_nodedup": t_nodedup / t_fwd,
         "speedup_vs_nodedup_incl_build": t_nodedup / (t_fwd + t_build),
         "nodedup_tokens_per_s": N / (t_nodedup * 1e-3),
+        "other_attention_mode": {"mode": "scatter -> attention -> gather" if fused else "fused",
+                                 "ms_per_step": t_step_other, "value": N / (t_step_other * 1e-3),
+                                 "forward_ms": t_fwd_other, "speedup_vs_nodedup": t_nodedup / t_fwd_other,
+                                 "attention_ms_per_forward": attn_other_ms},
         "kernel_ms_per_forward": {k: v[0] for k, v in per_kernel.items()},
         "compact_gemm_tflops": gemm_flops_layer * cfg.n_layers / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
         "compact_gemm_frac_of_peak": (gemm_flops_layer * cfg.n_layers / (gemm_ms * 1e-3) / 1e12 / peak) if gemm_ms > 0 else None,

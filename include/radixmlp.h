@@ -102,6 +102,13 @@ typedef struct radix_model radix_model;      /* opaque */
 typedef struct radix_fwd_opts {
     float threshold;      /* deduplicate iff n_compact < threshold * N; 1.0 = whenever anything is shared */
     int32_t force_dedup;  /* 1: always take the deduplicated path, whatever the threshold says */
+    int32_t fused_attention; /* 0: scatter -> attention on all N rows -> gather, three kernels, as Algorithm 1
+                              *    writes them.  1: one attention kernel that reads q, k, v of the compact
+                              *    buffer through I_scatter, computes only the representative positions (the
+                              *    rows the gather would keep) and writes compact rows; same values bit for
+                              *    bit, no [N, .] copies.  16-bit operand configurations only
+                              *    (RADIX_ERR_UNSUPPORTED otherwise); ignored when the threshold turns
+                              *    deduplication off. */
 } radix_fwd_opts;
 
 /*

@@ -49,7 +49,7 @@ class radix_weights(C.Structure):
 
 
 class radix_fwd_opts(C.Structure):
-    _fields_ = [("threshold", C.c_float), ("force_dedup", C.c_int32)]
+    _fields_ = [("threshold", C.c_float), ("force_dedup", C.c_int32), ("fused_attention", C.c_int32)]
 
 
 _LIB: Optional[C.CDLL] = None
@@ -193,11 +193,12 @@ def radix_build_index(tok: torch.Tensor, pos: Optional[torch.Tensor], cu_seqlens
 def radix_prefill_forward(model: Model, tok: torch.Tensor, pos: Optional[torch.Tensor], cu_seqlens: torch.Tensor,
                           max_seqlen: int, I_scatter: torch.Tensor, I_gather: torch.Tensor, n_compact: int,
                           ws: torch.Tensor, out: Optional[torch.Tensor] = None, threshold: float = 1.0,
-                          force_dedup: bool = False, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                          force_dedup: bool = False, stream: Optional[torch.cuda.Stream] = None,
+                          fused_attention: bool = False) -> torch.Tensor:
     N, B = tok.numel(), cu_seqlens.numel() - 1
     if out is None:
         out = torch.empty((N, model.cfg.d), dtype=torch.float32, device=cu_seqlens.device)
-    opts = radix_fwd_opts(threshold, int(force_dedup))
+    opts = radix_fwd_opts(threshold, int(force_dedup), int(fused_attention))
     rc = _lib().radix_prefill_forward(model.handle, _ptr(tok), _ptr(pos), _ptr(cu_seqlens), B, N, max_seqlen,
                                       _ptr(I_scatter), _ptr(I_gather), n_compact, C.byref(opts), _ptr(out),
                                       _ptr(ws), ws.numel(), _stream(stream))

@@ -20,6 +20,15 @@
 // per lane, 8 keys of one hd column out of the row-major V tile: that is what ds_read_b64_tr_b16
 // delivers - 16 lanes hand in the addresses of a 4-key x 16-column block (lane 4 e + a: key e, columns
 // 4 a .. 4 a + 3) and lane l receives column l of keys 0..3 - so V is never transposed in memory.
+//
+// FUSED mode (scatter and gather folded into this kernel; exact).  Q, K and V stay in the COMPACT
+// buffer: the row of sequence position p is I_scatter[start + p], looked up one tile ahead of the
+// K/V load that uses it.  Attention outputs at duplicate positions are thrown away by the gather
+// (Algorithm 1, "Gather attention output"), and in a trie the representative tokens of a sequence are
+// a SUFFIX of it (once a token opens a new node, so do all later ones), so the workgroups of a
+// sequence cover only positions [rep_start, len) and write their rows straight into the compact
+// attention output.  K/V tiles, their order and every row's arithmetic are those of the full-layout
+// mode, so both modes give bit-identical rows.
 #include "common.h"
 #include "kernels.h"
 
@@ -45,12 +54,15 @@ __device__ __forceinline__ uint32_t att_lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int DT, int HPB>
+template <int DT, int HPB, bool FUSED>
 __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
                                                                         const int32_t* __restrict__ cu, int N,
                                                                         int n_q_heads, int n_kv_heads, int n_qtiles,
                                                                         int n_pairs,
-                                                                        typename Op<DT>::T* __restrict__ out) {
+                                                                        typename Op<DT>::T* __restrict__ out,
+                                                                        const int32_t* __restrict__ iscat,
+                                                                        const int32_t* __restrict__ rep_start,
+                                                                        int n_compact) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
@@ -74,7 +86,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     start = start < 0 ? 0 : (start > N ? N : start);
     end = end < start ? start : (end > N ? N : end);
     const int len = end - start;
-    const int q0 = qt * BQ;
+    int q0 = qt * BQ;
+    if (FUSED) {
+        int first = rep_start[seq];                     // first representative position of the sequence
+        first = first < 0 ? 0 : first;
+        q0 += first;
+    }
     if (q0 >= len) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -87,32 +104,53 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     const int dq = n_q_heads * HD, dkv = n_kv_heads * HD;
     const size_t row = (size_t)dq + 2 * (size_t)dkv;
     const uint32_t row_bytes = (uint32_t)(row * sizeof(T));
-    const char* kbase = (const char*)(qkv + (size_t)start * row + dq + (size_t)kvh * HD);
+    const char* kbase = (const char*)(qkv + (FUSED ? (size_t)0 : (size_t)start * row) + dq + (size_t)kvh * HD);
     const char* vbase = kbase + (size_t)dkv * sizeof(T);
+    const int32_t* smap = FUSED ? iscat + start : nullptr;      // position -> compact row
+    auto compact_row = [&](int p) {                             // clamped: a bad map can never leave the buffer
+        int c = smap[p];
+        c = c < 0 ? 0 : (c >= n_compact ? n_compact - 1 : c);
+        return c;
+    };
 
     // ---- K/V tile loads: wavefront w fills tile rows [16 w, 16 w + 16) of K and of V, 4 rows (1 KB) per
     // instruction: lane L -> row 4 j + L / 16, LDS chunk L % 16, global chunk = LDS chunk ^ swizzle(row).
     // Rows past the end of the sequence are clamped (the causal mask hides them).
     const int lrow = lane >> 4, lpc = lane & 15;
+    int krow[4];                                                // FUSED: compact rows of this lane's 4 keys of the tile to issue
+    auto lookup_tile = [&](int kv0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int kr = kv0 + 16 * wave + 4 * j + lrow;
+            kr = kr < len ? kr : len - 1;
+            krow[j] = compact_row(kr);
+        }
+    };
     auto issue_tile = [&](int kv0, int stage) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = 16 * wave + 4 * j + lrow;             // tile row = key
             int kr = kv0 + r;
             kr = kr < len ? kr : len - 1;
-            const uint32_t rb = (uint32_t)kr * row_bytes;
+            const uint32_t rb = (uint32_t)(FUSED ? krow[j] : kr) * row_bytes;
             att_dma16(kbase, rb + 16u * (uint32_t)(lpc ^ (r & 15)), att_lds_addr(&Ks[stage][(16 * wave + 4 * j) * 16]));
             att_dma16(vbase, rb + 16u * (uint32_t)(lpc ^ ((r & 3) << 2)), att_lds_addr(&Vs[stage][(16 * wave + 4 * j) * 16]));
         }
     };
+    const int wave_qmin = q0 + wq * 32, wave_qmax = wave_qmin + 31;
+    const int last_q = (q0 + BQ - 1) < (len - 1) ? (q0 + BQ - 1) : (len - 1);
+    const int n_tiles = last_q / BKV + 1;
+    if (FUSED) lookup_tile(0);
     issue_tile(0, 0);
+    if (FUSED && n_tiles > 1) lookup_tile(BKV);
 
     // ---- Q fragment (B operand of S^T = K Q^T): lane (n, g) holds Q[query n][16 ks + 8 g .. +8]
     const int qi = q0 + wq * 32 + n;                    // query offset inside the sequence
     const int qi_c = qi < len ? qi : len - 1;
     V8 qf[8];
     {
-        const uint4* qp = (const uint4*)(qkv + (size_t)(start + qi_c) * row + (size_t)h * HD);
+        const size_t qrow = FUSED ? (size_t)compact_row(qi_c) : (size_t)(start + qi_c);
+        const uint4* qp = (const uint4*)(qkv + qrow * row + (size_t)h * HD);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 v = qp[ks * 2 + g];
@@ -128,10 +166,6 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     float m_run = -INFINITY, l_run = 0.f;
     const float sc = 1.4426950408889634f / sqrtf((float)HD);     // log2(e) / sqrt(hd), applied inside the exponent
 
-    const int wave_qmin = q0 + wq * 32, wave_qmax = wave_qmin + 31;
-    const int last_q = (q0 + BQ - 1) < (len - 1) ? (q0 + BQ - 1) : (len - 1);
-    const int n_tiles = last_q / BKV + 1;
-
     // transpose-read addressing of V (see the header): 16-lane group = lane / 16 -> g = group / 2,
     // 16-column half = group % 2; inside the group lane i = 4 e + a reads key e, columns 4 a .. 4 a + 3.
     const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_half = (lane >> 4) & 1;
@@ -146,6 +180,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
         att_wait_vmcnt<0>();                // this wavefront's share of tile t has landed
         __syncthreads();                    // everybody's has; everybody is done with tile t-1
         if (t + 1 < n_tiles) issue_tile(kv0 + BKV, st ^ 1);
+        if (FUSED && t + 2 < n_tiles) lookup_tile(kv0 + 2 * BKV);   // rows of tile t+2, waited for with tile t+1
         if (kv0 > wave_qmax) continue;      // whole tile is in this wavefront's future
 
         // ---- S^T = K Q^T : two 32-key blocks x 8 k-steps.  The K fragments are read from LDS four MFMAs
@@ -245,7 +280,8 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (qi < len) {
         const float inv = 1.0f / l_tot;
-        T* op = out + (size_t)(start + qi) * dq + (size_t)h * HD;
+        const size_t orow = FUSED ? (size_t)compact_row(qi) : (size_t)(start + qi);
+        T* op = out + orow * dq + (size_t)h * HD;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -260,30 +296,53 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
 
 }  // namespace
 
-int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream) {
+static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
+                                int n_kv_heads, int hd, void* out, int op_dtype, const int32_t* iscat,
+                                const int32_t* rep_start, int n_compact, hipStream_t stream) {
+    const bool fused = iscat != nullptr;
     if (N <= 0 || B <= 0) return RADIX_OK;
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
     if (max_seqlen <= 0) return RADIX_ERR_BAD_SIZE;
     if (op_dtype != RADIX_BF16 && op_dtype != RADIX_F16) return RADIX_ERR_UNSUPPORTED;
     if ((((uintptr_t)qkv | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
+    if (fused && (rep_start == nullptr || n_compact <= 0)) return RADIX_ERR_BAD_SIZE;
     const int group = n_q_heads / n_kv_heads;
     const int hpb = (group % 4 == 0) ? 4 : (group % 2 == 0 ? 2 : 1);    // query heads per workgroup
     const int n_qtiles = ceil_div(max_seqlen, 128 / hpb);
     const int n_pairs = (n_q_heads / hpb) * B;
     const long long n_blocks = (long long)ceil_div(n_pairs, 8) * 8 * n_qtiles;
     if (n_blocks > 0x7FFFFFFFLL) return RADIX_ERR_UNSUPPORTED;
-    // per-lane 32-bit byte offsets inside one sequence's K/V rows
-    if ((long long)max_seqlen * (n_q_heads + 2 * n_kv_heads) * HD * 2 >= (1LL << 32)) return RADIX_ERR_UNSUPPORTED;
+    // per-lane 32-bit byte offsets: inside one sequence's K/V rows, or (fused) inside the compact buffer
+    const long long span_rows = fused ? (long long)n_compact : (long long)max_seqlen;
+    if (span_rows * (n_q_heads + 2 * n_kv_heads) * HD * 2 >= (1LL << 32)) return RADIX_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)n_blocks), block(ATT_THREADS);
-#define RADIX_ATT(DT, HPB)                                                                                       \
-    hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,   \
-                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out)
+#define RADIX_ATT(DT, HPB, F)                                                                                      \
+    hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB, F>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,  \
+                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, rep_start, n_compact)
+#define RADIX_ATT_H(DT, F)                                                                                         \
+    do {                                                                                                           \
+        if (hpb == 4) RADIX_ATT(DT, 4, F); else if (hpb == 2) RADIX_ATT(DT, 2, F); else RADIX_ATT(DT, 1, F);       \
+    } while (0)
     if (op_dtype == RADIX_BF16) {
-        if (hpb == 4) RADIX_ATT(RADIX_BF16, 4); else if (hpb == 2) RADIX_ATT(RADIX_BF16, 2); else RADIX_ATT(RADIX_BF16, 1);
+        if (fused) RADIX_ATT_H(RADIX_BF16, true); else RADIX_ATT_H(RADIX_BF16, false);
     } else {
-        if (hpb == 4) RADIX_ATT(RADIX_F16, 4); else if (hpb == 2) RADIX_ATT(RADIX_F16, 2); else RADIX_ATT(RADIX_F16, 1);
+        if (fused) RADIX_ATT_H(RADIX_F16, true); else RADIX_ATT_H(RADIX_F16, false);
     }
+#undef RADIX_ATT_H
 #undef RADIX_ATT
     return RADIX_OK;
+}
+
+int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream) {
+    return launch_attention_any(qkv, cu, B, N, max_seqlen, n_q_heads, n_kv_heads, hd, out, op_dtype, nullptr, nullptr,
+                                0, stream);
+}
+
+int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
+                                const int32_t* rep_start, int B, int N, int n_compact, int max_seqlen, int n_q_heads,
+                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream) {
+    if (I_scatter == nullptr) return RADIX_ERR_BAD_SIZE;
+    return launch_attention_any(qkv_c, cu, B, N, max_seqlen, n_q_heads, n_kv_heads, hd, out_c, op_dtype, I_scatter,
+                                rep_start, n_compact, stream);
 }

@@ -70,3 +70,12 @@ void launch_attention_f32(const float* qkv, const int32_t* cu, int B, int N, int
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), head_dim 128.
 int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                           int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream);
+// The same attention with scatter and gather folded in: q | k | v rows are read from the COMPACT buffer
+// qkv_c[n_compact, dq + 2 dkv] through I_scatter, only the representative positions of a sequence
+// ([rep_start[b], len_b), see launch_rep_start) are computed, and their rows go straight to out_c[n_compact, dq].
+int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
+                                const int32_t* rep_start, int B, int N, int n_compact, int max_seqlen, int n_q_heads,
+                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream);
+// rep_start[b] = first position of sequence b whose token is its own representative (len_b if none).
+void launch_rep_start(const int32_t* cu, const int32_t* I_scatter, const int32_t* I_gather, int B, int N,
+                      int n_compact, int32_t* rep_start, hipStream_t stream);

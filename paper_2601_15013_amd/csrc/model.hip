@@ -75,7 +75,7 @@ __global__ void clear_status_kernel(int32_t* hdr) { hdr[0] = 0; }
 size_t esize(int dtype) { return dtype == RADIX_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t pos_full, ids_c, pos_c, h, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
+    size_t pos_full, ids_c, pos_c, rep_start, h, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
 };
 
 WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
@@ -89,6 +89,7 @@ WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
     L.pos_full = take(N * 4);
     L.ids_c = take(M * 4);
     L.pos_c = take(M * 4);
+    L.rep_start = take(B * 4);
     L.h = take(M * c.d * 4);
     L.a = take(M * c.d * es * (c.split_norm_out ? 2 : 1));
     L.qkv = take(M * row * es);
@@ -247,9 +248,11 @@ extern "C" int radix_device_status(void* ws, size_t ws_bytes, void* stream) {
 namespace {
 
 int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* pos, const int32_t* cu, int B, int N,
-                 int max_seqlen, const int32_t* Is, const int32_t* Ig, int M, bool dedup, float* out, void* ws,
-                 size_t ws_bytes, hipStream_t stream) {
+                 int max_seqlen, const int32_t* Is, const int32_t* Ig, int M, bool dedup, bool fused, float* out,
+                 void* ws, size_t ws_bytes, hipStream_t stream) {
     const radix_model_config& c = model->cfg;
+    if (fused && c.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;   // the fused kernel is the MFMA one
+    fused = fused && dedup;
     const WsLayout L = ws_layout(c, (size_t)N, (size_t)B);
     if (ws_bytes < L.total) return RADIX_ERR_WORKSPACE_TOO_SMALL;
     char* w = (char*)ws;
@@ -264,6 +267,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     int32_t* pos_full = (int32_t*)(w + L.pos_full);
     int32_t* ids_c = (int32_t*)(w + L.ids_c);
     int32_t* pos_c = (int32_t*)(w + L.pos_c);
+    int32_t* rep_start = (int32_t*)(w + L.rep_start);
     float* h = (float*)(w + L.h);
     void* a = w + L.a;
     void* qkv = w + L.qkv;
@@ -280,6 +284,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     }
     launch_compact_ids(tok, pos, dedup ? Ig : nullptr, M, N, c.vocab, c.max_pos, ids_c, pos_c, hdr, stream);
     launch_embed(model->embed, c.dtype, ids_c, M, d, h, stream);
+    if (fused) launch_rep_start(cu, Is, Ig, B, N, M, rep_start, stream);
 
     auto gemm = [&](const void* A, const void* W, int Nout, int K, int epi, void* o) -> int {
         if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream);
@@ -319,11 +324,17 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
             launch_qknorm_rope(qkv, dt, M, c.n_q_heads, c.n_kv_heads, hd, c.qk_norm, Lw.gq, Lw.gk, c.eps, pos_c,
                                model->cos_tab, model->sin_tab, stream);
         }
-        if (dedup) {   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
+        if (fused) {   // scatter, attention and gather in one kernel (exact): compact rows in, compact rows out
+            TimedScope t(RADIX_TIME_ATTENTION, stream);
+            rc = launch_attention_mfma_fused(qkv, cu, Is, rep_start, B, N, M, max_seqlen, c.n_q_heads, c.n_kv_heads,
+                                             hd, attn_c, dt, stream);
+            if (rc != RADIX_OK) return rc;
+        }
+        if (dedup && !fused) {   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
             TimedScope t(RADIX_TIME_SCATTER, stream);
             launch_index_select_rows(qkv, M, Is, N, (size_t)row * es, qkv_full, hdr, stream);
         }
-        {
+        if (!fused) {
             TimedScope t(RADIX_TIME_ATTENTION, stream);
             if (dt != RADIX_F32) {
                 rc = launch_attention_mfma(qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd, attn_full,
@@ -334,7 +345,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
                                      (float*)attn_full, stream);
             }
         }
-        if (dedup) {   // Gather(a)
+        if (dedup && !fused) {   // Gather(a)
             TimedScope t(RADIX_TIME_GATHER, stream);
             launch_index_select_rows(attn_full, N, Ig, M, (size_t)dq * es, attn_c, hdr, stream);
         }
@@ -397,9 +408,11 @@ extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* to
     const float threshold = opts ? opts->threshold : 1.0f;
     const bool force = opts ? opts->force_dedup != 0 : false;
     const bool dedup = force || ((double)n_compact < (double)threshold * (double)N);
+    const bool fused = opts ? opts->fused_attention != 0 : false;
+    if (opts && opts->fused_attention != 0 && opts->fused_attention != 1) return RADIX_ERR_BAD_CONFIG;
     if (!dedup) n_compact = N;
-    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, I_scatter, I_gather, n_compact, dedup, out, ws,
-                        ws_bytes, (hipStream_t)stream);
+    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, I_scatter, I_gather, n_compact, dedup, fused, out,
+                        ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int32_t* tok, const int32_t* pos,
@@ -407,8 +420,8 @@ extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int
                                              float* out, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_common(model, tok, cu_seqlens, B, N, max_seqlen, out, ws);
     if (rc != RADIX_OK) return rc;
-    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, out, ws, ws_bytes,
-                        (hipStream_t)stream);
+    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, false, out, ws,
+                        ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int radix_timing_enable(uint32_t category_mask, uint32_t every_nth) {

@@ -219,6 +219,33 @@ void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* id
     }
 }
 
+// First representative position of every sequence: the smallest p with I_gather[I_scatter[start + p]] ==
+// start + p, or len if the whole sequence duplicates earlier ones.  In a trie the predicate is monotone
+// along a sequence (a token that opens a new node makes every later token of the sequence open one
+// too), so a binary search finds it.  Map entries are clamped; a malformed map cannot fault.
+__global__ void rep_start_kernel(const int32_t* __restrict__ cu, const int32_t* __restrict__ Is,
+                                 const int32_t* __restrict__ Ig, int B, int N, int M, int32_t* __restrict__ rep) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int start = cu[b], end = cu[b + 1];
+    start = start < 0 ? 0 : (start > N ? N : start);
+    end = end < start ? start : (end > N ? N : end);
+    int lo = 0, hi = end - start;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        int c = Is[start + mid];
+        c = c < 0 ? 0 : (c >= M ? M - 1 : c);
+        if (Ig[c] == start + mid) hi = mid; else lo = mid + 1;
+    }
+    rep[b] = lo;
+}
+
+void launch_rep_start(const int32_t* cu, const int32_t* Is, const int32_t* Ig, int B, int N, int M, int32_t* rep,
+                      hipStream_t stream) {
+    if (B <= 0 || M <= 0) return;
+    hipLaunchKernelGGL(rep_start_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, stream, cu, Is, Ig, B, N, M, rep);
+}
+
 void launch_validate_cu(const int32_t* cu, int B, int N, int max_seqlen, int32_t* status, hipStream_t stream) {
     hipLaunchKernelGGL(validate_cu_kernel, dim3(ceil_div(B + 1, 256)), dim3(256), 0, stream, cu, B, N, max_seqlen,
                        status);
