@@ -30,6 +30,26 @@
 #include "common.h"
 #include "kernels.h"
 
+// Measurement probes, never defined in the library build: compile the main loop without its
+// global->LDS loads (RADIX_GEMM_PROBE_NO_LOADS), without its LDS fragment reads (.._NO_FRAGS) or
+// without its MFMAs (.._NO_MFMA) to time what remains (csrc/gemm_probe.hip).  Results are then
+// meaningless, addresses and control flow are unchanged.
+#ifdef RADIX_GEMM_PROBE_NO_FRAGS
+#define RADIX_PROBE_FRAG(x)
+#else
+#define RADIX_PROBE_FRAG(x) x
+#endif
+#ifdef RADIX_GEMM_PROBE_NO_LOADS
+#define RADIX_PROBE_LOAD(x)
+#else
+#define RADIX_PROBE_LOAD(x) x
+#endif
+#ifdef RADIX_GEMM_PROBE_NO_MFMA
+#define RADIX_PROBE_MFMA(ACC, FB, FA) asm volatile("" ::"v"(FB), "v"(FA))
+#else
+#define RADIX_PROBE_MFMA(ACC, FB, FA) ACC = Op<DT>::mfma(FB, FA, ACC)
+#endif
+
 namespace {
 
 constexpr int BK = 32;            // k-tile: 64 bytes = 4 chunks of 16 bytes per row
@@ -201,13 +221,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #define RADIX_MFMA_RANGE(FA, FB, LO, HI)                                                                           \
     do {                                                                                                           \
         _Pragma("unroll") for (int t = (LO); t < (HI); ++t)                                                        \
-            acc[t / MB][t % MB] = Op<DT>::mfma(FB[t / MB], FA[t % MB], acc[t / MB][t % MB]);                       \
+            RADIX_PROBE_MFMA(acc[t / MB][t % MB], FB[t / MB], FA[t % MB]);                                         \
     } while (0)
 
     // first k-step of the tile in stage CUR: its MFMAs, led by the fragment reads of its second k-step
 #define RADIX_HALF0(CUR)                                                                           \
         _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                        \
-            RADIX_FRAG1(CUR, 1, fa1, fb1, u);                                                      \
+            RADIX_PROBE_FRAG(RADIX_FRAG1(CUR, 1, fa1, fb1, u));                                    \
             RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);                  \
             __builtin_amdgcn_sched_barrier(0);                                                     \
         }                                                                                          \
@@ -216,31 +236,58 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 
     constexpr int UNITS = MB + NB;
     constexpr int HALF = MB * NB / 2;      // the reads ride on the first half of a k-step's MFMAs
-    static_assert(UNITS >= LOADS, "one pair of global->LDS loads per slice");
+    static_assert(UNITS >= A_LOADS && UNITS >= B_LOADS, "at most one pair of global->LDS loads per slice");
     V8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
     RADIX_ISSUE2(0, 0u, STAGE_B);
-    RADIX_ISSUE2(2, 2 * STAGE_B, 3 * STAGE_B);     // K = 64: tiles 0, 1 again, into stages nobody reads
-    wait_vmcnt<LOADS * 2>();
+    {   // activation half of the pair (2, 3); K = 64: tiles 0, 1 again, into stages nobody reads
+        const int ka = 2 < KT ? 2 : KT - 2;
+#pragma unroll
+        for (int f = 0; f < A_LOADS; ++f) {
+            RADIX_DMA1(ka, 2 * STAGE_B, f);
+            RADIX_DMA1(ka + 1, 3 * STAGE_B, f);
+        }
+    }
+    wait_vmcnt<A_LOADS * 2>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
+#ifdef RADIX_GEMM_PROBE_NO_FRAGS
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 1, fa1, fb1, u);
+#endif
 
     // One k-tile = two k-steps of 16, software-pipelined over two fragment register sets and
     // scheduled by hand (the scheduling barriers pin the order): the first half of a k-step's MFMAs
     // is cut into UNITS slices, each led by one LDS fragment read for the NEXT k-step; the second half
     // of the MFMAs then covers the LDS latency of those reads, so the matrix pipe always has queued work.
-    // K-tiles travel in PAIRS (t even, t+1).  The even tile needs neither wait nor barrier: its
-    // successor landed with the previous pair's barrier.  Between the two k-steps of the odd tile: wait
-    // for this wavefront's loads of the pair (t+2, t+3), barrier (everybody's share has landed and
-    // everybody is past tile t), then refill the stages of tiles t-1 and t with the pair (t+4, t+5),
-    // two loads per slice.  Pairs past the end re-fetch the last pair into those two stages, which
-    // nobody reads again: the loop body has no branch.
-    uint32_t so_e = 0, so_o = STAGE_B, so_n = 2 * STAGE_B, so_ra = 4 * STAGE_B;   // stages of t, t+1, t+2, t+4
+    // K-tiles travel in PAIRS (t even, t+1) and their loads are spread thinly over the MFMA stream (a
+    // wavefront that has to wait for room in the memory pipeline cannot issue MFMAs meanwhile):
+    //   * first k-step of the even tile: the WEIGHT rows of the pair (t+2, t+3);
+    //   * between the two k-steps of the odd tile: wait for this wavefront's loads of the pair
+    //     (t+2, t+3), barrier (everybody's share has landed and everybody is done with the pair
+    //     (t, t+1)), then, along the second k-step, the ACTIVATION rows of the pair (t+4, t+5) into
+    //     the stages of tiles t-1 and t.
+    // Pairs past the end re-fetch the last pair into stages nobody reads again: no branch in the body.
+    uint32_t so_e = 0, so_o = STAGE_B, so_n = 2 * STAGE_B, so_n1 = 3 * STAGE_B, so_ra = 4 * STAGE_B;   // t, t+1, t+2, t+3, t+4
     for (int kt = 0; kt < KT; kt += 2) {
-        RADIX_HALF0(so_e)
+        const int kw = kt + 2 < KT ? kt + 2 : KT - 2;
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
-            RADIX_FRAG1(so_o, 0, fa0, fb0, u);
+#pragma unroll
+            for (int dd = 0; dd < 2 * B_LOADS; ++dd)        // load dd: row group dd / 2 of tile t+2 + dd % 2
+                if (dd * UNITS / (2 * B_LOADS) == u) {
+                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(kw, so_n, A_LOADS + dd / 2));
+                    else RADIX_PROBE_LOAD(RADIX_DMA1(kw + 1, so_n1, A_LOADS + dd / 2));
+                }
+            RADIX_PROBE_FRAG(RADIX_FRAG1(so_e, 1, fa1, fb1, u));
+            RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        RADIX_MFMA_RANGE(fa0, fb0, HALF, MB * NB);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            RADIX_PROBE_FRAG(RADIX_FRAG1(so_o, 0, fa0, fb0, u));
             RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -253,9 +300,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         const int ka = kt + 4 < KT ? kt + 4 : KT - 2;
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
-            RADIX_DMA1(ka, so_ra, u);
-            RADIX_DMA1(ka + 1, so_e, u);           // tile t+5 goes where tile t was
-            RADIX_FRAG1(so_n, 0, fa0, fb0, u);
+#pragma unroll
+            for (int dd = 0; dd < 2 * A_LOADS; ++dd)
+                if (dd * UNITS / (2 * A_LOADS) == u) {
+                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(ka, so_ra, dd / 2));
+                    else RADIX_PROBE_LOAD(RADIX_DMA1(ka + 1, so_e, dd / 2));       // tile t+5 goes where tile t was
+                }
+            RADIX_PROBE_FRAG(RADIX_FRAG1(so_n, 0, fa0, fb0, u));
             RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -266,8 +317,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         so_e = so_n;
         so_o = so_n + STAGE_B == 5 * STAGE_B ? 0u : so_n + STAGE_B;
         so_n = so_o + STAGE_B == 5 * STAGE_B ? 0u : so_o + STAGE_B;
-        so_ra = so_n + STAGE_B == 5 * STAGE_B ? 0u : so_n + STAGE_B;
-        so_ra = so_ra + STAGE_B == 5 * STAGE_B ? 0u : so_ra + STAGE_B;
+        so_n1 = so_n + STAGE_B == 5 * STAGE_B ? 0u : so_n + STAGE_B;
+        so_ra = so_n1 + STAGE_B == 5 * STAGE_B ? 0u : so_n1 + STAGE_B;
     }
 #undef RADIX_HALF0
 #undef RADIX_ISSUE2
@@ -341,7 +392,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
                                 const float gt = acc[j][ip + il][q * 4 + t], up = acc[j + 1][ip + il][q * 4 + t];
-                                v[t] = (T)(gt / (1.0f + __expf(-gt)) * up);
+                                // silu(g) * u with the hardware reciprocal (1 ulp) instead of an IEEE division
+                                v[t] = (T)(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up);
                             }
                             *reinterpret_cast<V4*>(rowp + ((j >> 1) * 32 + 8 * q + 4 * g) * 2) = v;
                         }
