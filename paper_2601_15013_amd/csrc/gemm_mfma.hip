@@ -97,11 +97,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
     static_assert(EPI != EPI_SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
     static_assert(EPI != EPI_QKV_ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
-    static_assert(LOADS * 4 < 64, "vmcnt range");
+    static_assert(LOADS * 2 + (BM / 64) * 2 < 64, "vmcnt range");
 
     constexpr int EPI_PITCH = 272;                             // epilogue row pitch in bytes (256 + 16 pad)
     constexpr int EPI_SLOTS = 4 * 64 * EPI_PITCH / 16;         // 4 wavefronts x 64 rows
-    constexpr int LDS_SLOTS = 5 * STAGE > EPI_SLOTS ? 5 * STAGE : EPI_SLOTS;
+    // ring of k-tile stages: six where they fit the 160 KB of LDS (the smaller tiles), else five
+    constexpr int NS = (6 * STAGE * 16 <= 160 * 1024) ? 6 : 5;
+    constexpr int LDS_SLOTS = NS * STAGE > EPI_SLOTS ? NS * STAGE : EPI_SLOTS;
     __shared__ uint4 lds_all[LDS_SLOTS];
 
     // ---- tile assignment: XCD-aware renumbering, then row-tile bands of 8 sweeping the columns
@@ -238,6 +240,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int HALF = MB * NB / 2;      // the reads ride on the first half of a k-step's MFMAs
     static_assert(UNITS >= A_LOADS && UNITS >= B_LOADS, "at most one pair of global->LDS loads per slice");
     V8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
+    if constexpr (NS == 5) {
     RADIX_ISSUE2(0, 0u, STAGE_B);
     {   // activation half of the pair (2, 3); K = 64: tiles 0, 1 again, into stages nobody reads
         const int ka = 2 < KT ? 2 : KT - 2;
@@ -319,6 +322,81 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         so_n = so_o + STAGE_B == 5 * STAGE_B ? 0u : so_o + STAGE_B;
         so_n1 = so_n + STAGE_B == 5 * STAGE_B ? 0u : so_n + STAGE_B;
         so_ra = so_n1 + STAGE_B == 5 * STAGE_B ? 0u : so_n1 + STAGE_B;
+    }
+    } else {
+    // Six stages = three pair slots: the loads of a pair are issued two pair-iterations before they
+    // are waited for (one with five stages), which the short k-tiles of the small workgroup tiles need.
+    // Iteration p (tiles t = 2p, t+1): weight rows of pair p+2 along the first k-step of the even tile;
+    // between the k-steps of the odd tile wait for pair p+1 (pair p+2 may stay in flight), barrier, then
+    // the activation rows of pair p+3 into the stages of pair p.
+    RADIX_ISSUE2(0, 0u, STAGE_B);
+    RADIX_ISSUE2(2, 2 * STAGE_B, 3 * STAGE_B);
+    {
+        const int ka = 4 < KT ? 4 : KT - 2;
+#pragma unroll
+        for (int f = 0; f < A_LOADS; ++f) {
+            RADIX_DMA1(ka, 4 * STAGE_B, f);
+            RADIX_DMA1(ka + 1, 5 * STAGE_B, f);
+        }
+    }
+    wait_vmcnt<LOADS * 2 + A_LOADS * 2>();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
+#ifdef RADIX_GEMM_PROBE_NO_FRAGS
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 1, fa1, fb1, u);
+#endif
+    uint32_t so_e = 0, so_n = 2 * STAGE_B, so_w = 4 * STAGE_B;      // stages of t, t+2, t+4 (pairs are adjacent)
+    for (int kt = 0; kt < KT; kt += 2) {
+        const int kw = kt + 4 < KT ? kt + 4 : KT - 2;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+#pragma unroll
+            for (int dd = 0; dd < 2 * B_LOADS; ++dd)
+                if (dd * UNITS / (2 * B_LOADS) == u) {
+                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(kw, so_w, A_LOADS + dd / 2));
+                    else RADIX_PROBE_LOAD(RADIX_DMA1(kw + 1, so_w + STAGE_B, A_LOADS + dd / 2));
+                }
+            RADIX_PROBE_FRAG(RADIX_FRAG1(so_e, 1, fa1, fb1, u));
+            RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        RADIX_MFMA_RANGE(fa0, fb0, HALF, MB * NB);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            RADIX_PROBE_FRAG(RADIX_FRAG1(so_e + STAGE_B, 0, fa0, fb0, u));
+            RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        RADIX_MFMA_RANGE(fa1, fb1, HALF, MB * NB);
+        __builtin_amdgcn_sched_barrier(0);
+
+        RADIX_HALF0(so_e + STAGE_B)
+        wait_vmcnt<LOADS * 2>();
+        __builtin_amdgcn_s_barrier();
+        const int ka = kt + 6 < KT ? kt + 6 : KT - 2;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+#pragma unroll
+            for (int dd = 0; dd < 2 * A_LOADS; ++dd)
+                if (dd * UNITS / (2 * A_LOADS) == u) {
+                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(ka, so_e, dd / 2));
+                    else RADIX_PROBE_LOAD(RADIX_DMA1(ka + 1, so_e + STAGE_B, dd / 2));
+                }
+            RADIX_PROBE_FRAG(RADIX_FRAG1(so_n, 0, fa0, fb0, u));
+            RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        RADIX_MFMA_RANGE(fa1, fb1, HALF, MB * NB);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // rotate by one pair slot
+        so_e = so_n;
+        so_n = so_w;
+        so_w = so_w + 2 * STAGE_B == 6 * STAGE_B ? 0u : so_w + 2 * STAGE_B;
+    }
     }
 #undef RADIX_HALF0
 #undef RADIX_ISSUE2
