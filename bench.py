@@ -22,7 +22,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 
 # HBM-side bytes per gate/up GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled
 # by the 256 MiB copy dispatch of the same run (profiles/gemm_gateup_C2_hbm_traffic.md); None where not measured.
-GATEUP_TRAFFIC_BYTES = {"C2": int(82710 * 1024 * 1.984 + 47202 * 1024)}
+GATEUP_TRAFFIC_BYTES = {"C2": int(82646 * 1024 * 1.984 + 47202 * 1024)}
 
 WORKLOAD_TEXT = {
     "C1": "C1: tiny Qwen3-style decoder fp32, 8 seqs = 32 shared + 16 own tokens",
@@ -43,6 +43,9 @@ def main() -> int:
     ap.add_argument("--fused-attention", action="store_true",
                     help="time the mode with scatter/gather folded into the attention kernel (default: the "
                          "three-kernel scatter -> attention -> gather path of Algorithm 1)")
+    ap.add_argument("--split-norm-out", choices=["auto", "0", "1", "2"], default="auto",
+                    help="hi/lo RMSNorm outputs (1: both norms, 2: pre-attention norm only); auto = the setting the "
+                         "configuration's parity test runs with (2 for C4, 0 elsewhere)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough budget of the oracle timing")
     args = ap.parse_args()
@@ -64,6 +67,10 @@ def main() -> int:
     key = args.workload
     batch = synth.make_batch(key)
     weights = synth.make_weights(key)
+    split = (2 if key == "C4" else 0) if args.split_norm_out == "auto" else int(args.split_norm_out)
+    if split:
+        import dataclasses
+        weights = synth.SynthWeights(dataclasses.replace(weights.cfg, split_norm_out=split), weights.seed)
     cfg = weights.cfg
     model = harness.upload_model(weights)
     run = harness.Runner(model, batch.N, batch.B)
@@ -163,6 +170,7 @@ def main() -> int:
         "config": {"workload": WORKLOAD_TEXT[key], "B": B, "N": N, "N_compact": n_c,
                    "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": synth.WORKLOADS[key].seed,
                    "weights": cfg.dtype, "operands": cfg.compute_dtype, "accumulate": "f32",
+                   "split_norm_out": int(cfg.split_norm_out),
                    "attention_mode": "fused (indexed q/k/v, representative rows only)" if fused
                    else "scatter -> attention over N rows -> gather"},
         "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
@@ -182,7 +190,8 @@ def main() -> int:
         "roofline": {"kernel": "gate/up GEMM + SwiGLU (M=N', N=2*d_int, K=d)", "bound": "mfma", "achieved": achieved,
                      "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": GATEUP_TRAFFIC_BYTES.get(key),
-                     "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom},
+                     "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom,
+                     "executed_flops_per_launch": flops_dom * (2 if cfg.split_norm_out == 1 else 1)},
     }
 
     if not args.no_cpu_baseline:

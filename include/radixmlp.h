@@ -64,11 +64,12 @@ typedef struct radix_model_config {
                               RADIX_F16 converts the weights once at create time (exact for every bf16
                               value of magnitude >= 2^-17) and carries 11-bit instead of 8-bit
                               significands through the activations; activations must stay below 65504. */
-    int32_t split_norm_out; /* 0 or 1 (bf16 weights only, d a multiple of 256).  1: the two RMSNorm outputs of a layer
-                              are carried as a 16-bit (hi, lo) pair and the Q/K/V and gate/up GEMMs run over the doubled
-                              K against the weights read twice: about twice the significand on the activations that
-                              dominate the rounding error, for about twice the work in those two GEMMs.  For deep,
-                              wide random-init models whose layers amplify perturbations. */
+    int32_t split_norm_out; /* 0, 1 or 2 (bf16 weights only, d a multiple of 256).  Carries RMSNorm outputs as a 16-bit
+                              (hi, lo) pair and runs the GEMM they feed over the doubled K against the weights read
+                              twice: about twice the significand on the activations that dominate the rounding
+                              error, for twice the work in that GEMM.  1: both norms of a layer (Q/K/V and gate/up
+                              GEMMs doubled); 2: the pre-attention norm only (Q/K/V GEMM doubled).  For deep, wide
+                              random-init models whose layers amplify perturbations. */
     float eps;           /* RMSNorm epsilon (inside the square root) */
     float rope_base;
 } radix_model_config;

@@ -114,7 +114,7 @@ int check_config(const radix_model_config& c) {
     if (c.head_dim % 2 != 0 || c.head_dim > 128) return RADIX_ERR_UNSUPPORTED;
     if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
     if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
-    if (c.split_norm_out != 0 && c.split_norm_out != 1) return RADIX_ERR_BAD_CONFIG;
+    if (c.split_norm_out < 0 || c.split_norm_out > 2) return RADIX_ERR_BAD_CONFIG;
     if (c.split_norm_out && (c.dtype != RADIX_BF16 || c.d % 256 != 0)) return RADIX_ERR_UNSUPPORTED;
     if (c.dtype == RADIX_BF16) {
         // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 32 and every
@@ -295,7 +295,8 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     int rc = RADIX_OK;
     for (int l = 0; l < c.n_layers; ++l) {
         const radix_layer_dev& Lw = model->layers[l];
-        const int ka = c.split_norm_out ? 2 * d : d;     // K of the GEMMs fed by an RMSNorm
+        const int ka = c.split_norm_out ? 2 * d : d;          // K of the QKV GEMM
+        const int kb = c.split_norm_out == 1 ? 2 * d : d;     // K of the gate/up GEMM
         {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
             if (c.split_norm_out) {
@@ -355,7 +356,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
-            if (c.split_norm_out) {
+            if (c.split_norm_out == 1) {
                 if ((rc = launch_rmsnorm_split(h, Lw.g2, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
             } else {
                 launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
@@ -364,7 +365,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         {
             TimedScope t(RADIX_TIME_GEMM_GATEUP, stream);
             if (dt != RADIX_F32)
-                rc = launch_gemm_mfma(a, Lw.wgu, M, 2 * c.d_int, ka, EPI_SWIGLU, mlp, dt, 0, stream, nullptr, d);
+                rc = launch_gemm_mfma(a, Lw.wgu, M, 2 * c.d_int, kb, EPI_SWIGLU, mlp, dt, 0, stream, nullptr, d);
             else
                 rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp);
             if (rc != RADIX_OK) return rc;

@@ -88,6 +88,7 @@ def test_model_create_rejects_bad_config(lib):
     assert create(dtype=1, compute_dtype=1) == -3    # 16-bit path needs head_dim 128
     assert create(compute_dtype=2) == -3         # fp32 weights are multiplied in fp32
     assert create(split_norm_out=1) == -3        # hi/lo activations exist for 16-bit operands only
+    assert create(split_norm_out=2) == -3
     assert create(split_norm_out=5) == -9
     assert create(dtype=1, compute_dtype=0, head_dim=128) == -3
     assert create(d_int=100) == -3               # gate/up interleave needs multiples of 32

@@ -102,7 +102,7 @@ def test_bf16_small_model_several_tiles_and_ragged_tail(compute, tol):
 def test_split_norm_outputs_tighten_the_error():
     # hi/lo RMSNorm outputs: same result to a tighter error, still row-invariant
     errs = {}
-    for split in (False, True):
+    for split in (0, 2, 1):     # off, pre-attention norm only, both norms
         cfg = dataclasses.replace(SMALL_BF16, compute_dtype="bf16", split_norm_out=split)
         w = synth.SynthWeights(cfg, 31)
         b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, cfg.vocab)
@@ -111,8 +111,9 @@ def test_split_norm_outputs_tighten_the_error():
         errs[split] = float(np.sqrt(np.mean((y - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))     # RMS error: stable
         assert U.rel_err(y, ref) <= TOL_BF16_OPERANDS
         assert np.array_equal(y, y_nd)
-    print("bf16 operands, relative RMS error with split off/on:", errs)
-    assert errs[True] < 0.9 * errs[False]
+    print("bf16 operands, relative RMS error with split off / pre-attention / both:", errs)
+    assert errs[1] < 0.9 * errs[0]
+    assert errs[1] < errs[2] < errs[0]
 
 
 def test_bf16_wide_model_uses_large_gemm_tiles():
@@ -181,7 +182,7 @@ def test_empty_batch_and_bad_inputs():
     model.close()
 
 
-def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None, split=False):
+def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None, split=0):
     """Full-size batch on the GPU in the benchmark's launch configuration; the oracle computes
     whole sampled sequences (the no-dedup pass is independent per sequence)."""
     b = synth.make_batch(key)
@@ -189,7 +190,7 @@ def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None, split=False):
     if compute is not None:
         w = synth.SynthWeights(dataclasses.replace(w.cfg, compute_dtype=compute), w.seed)
     if split:
-        w = synth.SynthWeights(dataclasses.replace(w.cfg, split_norm_out=True), w.seed)
+        w = synth.SynthWeights(dataclasses.replace(w.cfg, split_norm_out=split), w.seed)
     y, y_nd, n_c = run_all(w, b, force_dedup=True)
     assert n_c == b.expected_n_compact
     rows = U.rows_of(b, sequences)
@@ -213,8 +214,9 @@ def test_c3_full_size_sampled_sequences():
 def test_c4_full_size_sampled_sequences():
     # 8B shape, 256 sequences.  With N(0, 0.02) weights at d = 4096 every layer amplifies perturbations
     # (projection gain 0.02 * sqrt(4096) = 1.28 > 1), so fp16 activation rounding that costs 3e-3 on the
-    # 0.6B shape reaches ~2.1e-2 here after 36 layers; the hi/lo RMSNorm outputs bring it back under the bar.
-    _sampled_parity("C4", [0, 255], split=True)
+    # 0.6B shape reaches ~2.1e-2 here after 36 layers; a hi/lo pre-attention RMSNorm output (the largest single
+    # share of that variance, 29 %) brings it to ~1.7e-2 for one doubled GEMM.
+    _sampled_parity("C4", [0, 255], split=2)
 
 
 def test_c5_full_size_sampled_sequences():
