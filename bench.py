@@ -31,7 +31,10 @@ WORKLOAD_TEXT = {
     "C4": "C4: Qwen3-8B shape, reranking batch of 256 seqs = 64 shared + suffix U[96,256]",
     "C5": "C5: Qwen3-0.6B shape, 128 seqs = 2048-token shared prefix + 32 own tokens",
     "C5ctl": "C5 control: Qwen3-0.6B shape, 128 x 2080 tokens, no sharing, dedup forced on",
+    "SWEEP": "paper's synthetic sweep point (Experiments, forward-pass benchmark): B = 32 sequences = one shared prefix + "
+             "distinct fixed-length suffixes",
 }
+SWEEP_SEED = 2001
 
 
 def main() -> int:
@@ -46,6 +49,9 @@ def main() -> int:
     ap.add_argument("--split-norm-out", choices=["auto", "0", "1", "2"], default="auto",
                     help="hi/lo RMSNorm outputs (1: both norms, 2: pre-attention norm only); auto = the setting the "
                          "configuration's parity test runs with (2 for C4, 0 elsewhere)")
+    ap.add_argument("--sweep-model", choices=["0.6B", "4B", "8B"], default="0.6B", help="--workload SWEEP: model shape")
+    ap.add_argument("--sweep-prefix", type=int, default=2048, help="--workload SWEEP: shared prefix length")
+    ap.add_argument("--sweep-suffix", type=int, default=256, help="--workload SWEEP: suffix length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough budget of the oracle timing")
     args = ap.parse_args()
@@ -65,8 +71,14 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     key = args.workload
-    batch = synth.make_batch(key)
-    weights = synth.make_weights(key)
+    if key == "SWEEP":
+        model_cfg = {"0.6B": synth.QWEN3_0_6B, "4B": synth.QWEN3_4B, "8B": synth.QWEN3_8B}[args.sweep_model]
+        batch = synth.shared_prefix_batch(SWEEP_SEED, 32, args.sweep_prefix, args.sweep_suffix, args.sweep_suffix,
+                                          model_cfg.vocab, name="sweep")
+        weights = synth.SynthWeights(model_cfg, SWEEP_SEED)
+    else:
+        batch = synth.make_batch(key)
+        weights = synth.make_weights(key)
     split = (2 if key == "C4" else 0) if args.split_norm_out == "auto" else int(args.split_norm_out)
     if split:
         import dataclasses
@@ -167,8 +179,9 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": cfg.compute_dtype,
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[key], "B": B, "N": N, "N_compact": n_c,
-                   "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": synth.WORKLOADS[key].seed,
+        "config": {"workload": WORKLOAD_TEXT[key] + (f" - Qwen3-{args.sweep_model} shape, prefix {args.sweep_prefix}, "
+                                                     f"suffix {args.sweep_suffix}" if key == "SWEEP" else ""), "B": B, "N": N, "N_compact": n_c,
+                   "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": SWEEP_SEED if key == "SWEEP" else synth.WORKLOADS[key].seed,
                    "weights": cfg.dtype, "operands": cfg.compute_dtype, "accumulate": "f32",
                    "split_norm_out": int(cfg.split_norm_out),
                    "attention_mode": "fused (indexed q/k/v, representative rows only)" if fused
