@@ -569,13 +569,32 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
 template <int DT>
 int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out, int variant,
               const QkvEpilogue& qe, hipStream_t stream) {
-    // tile choice: the biggest tile that still gives every CU work
-    const long long t256 = (long long)ceil_div(M, 256) * (Nout / 256);
+    // Tile choice by a small cost model: workgroups run one per CU in rounds, a round costs a fixed part
+    // (launch, first loads, epilogue) plus the k-tiles at the rate measured for that tile shape
+    // (microseconds per 32-wide k-tile on MI355X, random fp16 operands): a launch that does not fill its
+    // last round pays for it in full, which is what decides between the shapes for small M * Nout.
     if (variant == 0) {
-        if (Nout % 256 == 0 && t256 >= 200) variant = 1;           // 256 x 256: least L2 traffic per flop
-        else if (Nout % 256 == 0 && 2 * t256 >= 128) variant = 3;  // 128 x 256: twice the workgroups
-        else variant = 2;
-        if (epilogue == EPI_QKV_ROPE && variant == 2) variant = 3;   // needs 128-wide wavefront blocks
+        static int n_cu = 0;
+        if (n_cu == 0) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+                cus = 256;
+            n_cu = cus;
+        }
+        struct Shape { int variant, bm, bn; double fixed_us, ktile_us; };
+        static const Shape shapes[3] = {{1, 256, 256, 9.0, 0.83}, {3, 128, 256, 7.0, 0.57}, {2, 128, 128, 5.0, 0.29}};
+        double best = 0.0;
+        for (const Shape& sh : shapes) {
+            if (Nout % sh.bn != 0) continue;
+            if (epilogue == EPI_QKV_ROPE && sh.bn != 256) continue;      // needs 128-wide wavefront blocks
+            const double tiles = (double)ceil_div(M, sh.bm) * (Nout / sh.bn);
+            double rounds = tiles / n_cu;
+            if (rounds < 8.0) rounds = (double)(long long)(rounds + 0.999999);   // few rounds: the last one counts whole
+            const double t = rounds * (sh.fixed_us + (K / BK) * sh.ktile_us);
+            if (variant == 0 || t < best) { best = t; variant = sh.variant; }
+        }
+        if (variant == 0) return RADIX_ERR_UNSUPPORTED;
     }
     if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
     if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
