@@ -35,6 +35,9 @@ WORKLOAD_TEXT = {
              "distinct fixed-length suffixes",
 }
 SWEEP_SEED = 2001
+WORKLOAD_TEXT["INDEXSELECT"] = "row index-select at the shapes of the paper's gather/scatter kernel benchmark (Appendix, index-select kernel)"
+# (source rows, row elements, selected rows)
+INDEX_SELECT_SHAPES = [(16000, 1024, 12000), (16000, 1024, 70000), (100000, 2048, 500000), (2000, 64 * 256, 10000)]
 
 
 def main() -> int:
@@ -71,6 +74,8 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     key = args.workload
+    if key == "INDEXSELECT":
+        return index_select_bench(args, torch, np, binding)
     if key == "SWEEP":
         model_cfg = {"0.6B": synth.QWEN3_0_6B, "4B": synth.QWEN3_4B, "8B": synth.QWEN3_8B}[args.sweep_model]
         batch = synth.shared_prefix_batch(SWEEP_SEED, 32, args.sweep_prefix, args.sweep_suffix, args.sweep_suffix,
@@ -212,6 +217,37 @@ def main() -> int:
 
     model.close()
     print(json.dumps(result))
+    return 0
+
+
+def index_select_bench(args, torch, np, binding):
+    """out[r] = src[idx[r]] with seeded uniform indices: time per call and moved bytes (read + written) per second."""
+    rows = []
+    rng = np.random.Generator(np.random.Philox(key=[3001, 0x1D5E]))
+    for n_src, width, n_out in INDEX_SELECT_SHAPES:
+        for dt, name in ((torch.float16, "f16"), (torch.float32, "f32")):
+            src = torch.empty((n_src, width), dtype=dt, device="cuda").normal_()
+            idx = torch.from_numpy(rng.integers(0, n_src, size=n_out, dtype=np.int64).astype(np.int32)).cuda()
+            out = torch.empty((n_out, width), dtype=dt, device="cuda")
+            for _ in range(args.warmup):
+                binding.radix_index_select_rows(src, idx, out=out)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                binding.radix_index_select_rows(src, idx, out=out)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t0) * 1e6 / args.steps
+            moved = 2.0 * n_out * width * src.element_size()
+            rows.append({"src_rows": n_src, "row_elems": width, "out_rows": n_out, "dtype": name, "us": us,
+                         "GBps": moved / us / 1e3})
+            del src, idx, out
+    big = rows[-3]      # [100000, 2048] -> 500000 rows, f32: the largest transfer
+    print(json.dumps({"metric": "index-select throughput (bytes read + written)", "value": big["GBps"], "unit": "GB/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": big["us"] * 1e-3,
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+                      "data": "synthetic", "config": {"workload": WORKLOAD_TEXT["INDEXSELECT"]}, "shapes": rows,
+                      "roofline": {"bound": "hbm", "achieved": big["GBps"], "peak": 8000.0, "unit": "GB/s",
+                                   "frac": big["GBps"] / 8000.0, "traffic": None}}))
     return 0
 
 
