@@ -24,7 +24,8 @@ What is computed, per sequence with tokens t_0..t_{n-1} and positions p_i (defau
 Readings where the paper is silent (all listed in DESIGN.md): the paper's "LayerNorm" is
 RMSNorm x * rsqrt(mean(x^2) + eps) * g with eps inside the square root; RoPE pairs element i
 with i + hd/2, angle p * base^(-2i/hd); softmax scale 1/sqrt(hd); silu(z) = z / (1 + exp(-z));
-the output is the final-norm hidden state (the LM head is not part of this path).
+the output is the final-norm hidden state; ``lm_head_logits`` is Algorithm 1's tail (logits = LMHead(h)) for
+the rows a caller selects, with the head tied to the embedding when no separate matrix is given.
 
 Pins (tests/test_oracle_forward.py): a composition of torch's own library routines
 (embedding, rms_norm, linear, scaled_dot_product_attention(is_causal), silu, complex-number
@@ -145,3 +146,17 @@ def forward_nodedup(cfg: Any, embed: Any, layers: Iterable[Mapping[str, Any]], g
     if not out:
         return np.zeros((0, cfg.d), dtype=np.float64)
     return torch.cat(out, dim=0).numpy()
+
+
+def lm_head_logits(hidden: Any, w_lm: Any, rows: Any = None, dtype: torch.dtype = torch.float64) -> np.ndarray:
+    """Algorithm 1, last block ("Output"): logits = LMHead(h), a bias-free linear map.
+
+    hidden[n, d]: final-norm hidden states (what ``forward_nodedup`` returns); w_lm[vocab, d]: the
+    head in [out, in] layout like every other matrix here (the embedding matrix itself when the head
+    is tied); rows: optional indices into hidden (e.g. the last token of every sequence, or I_gather
+    for logits in compact space).  Returns logits[len(rows) or n, vocab] = hidden[rows] @ w_lm^T.
+    """
+    h = _t(hidden, dtype)
+    if rows is not None:
+        h = h[torch.as_tensor(np.asarray(rows, dtype=np.int64))]
+    return torch.matmul(h, _t(w_lm, dtype).T).numpy()

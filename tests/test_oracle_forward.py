@@ -242,3 +242,37 @@ def test_float32_mode_is_close_to_float64():
     y64 = _run(cfg, wts, tok, [0, 10])
     y32 = _run(cfg, wts, tok, [0, 10], dtype=torch.float32)
     assert np.max(np.abs(y64 - y32)) < 1e-4
+
+
+def test_lm_head_is_the_plain_linear_map():
+    # pinned by the definition written as explicit sums, by unit vectors (a one-hot hidden state reads out
+    # a column of the head) and by row selection commuting with the product
+    rng = np.random.default_rng(7)
+    hidden = rng.standard_normal((5, 6))
+    w = rng.standard_normal((9, 6))
+    got = orc.lm_head_logits(hidden, w)
+    want = np.zeros((5, 9))
+    for i in range(5):
+        for v in range(9):
+            for k in range(6):
+                want[i, v] += hidden[i, k] * w[v, k]
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+    eye = np.eye(6)
+    np.testing.assert_array_equal(orc.lm_head_logits(eye, w), w.T)
+    rows = [4, 0, 0, 2]
+    np.testing.assert_array_equal(orc.lm_head_logits(hidden, w, rows=rows), got[rows])
+    assert orc.lm_head_logits(hidden, w, rows=[]).shape == (0, 9)
+
+
+def test_lm_head_in_compact_space_then_scatter_equals_head_on_all_rows():
+    # Algorithm 1's tail: y_c = LMHead(h_c), y = Scatter(y_c).  With the maps of a shared-prefix batch and
+    # hidden states that are equal on duplicate rows (which the forward guarantees), both orders agree exactly.
+    from oracle import radix_index as oracle_index
+    b = synth.shared_prefix_batch(5, 4, 6, 2, 5, 50)
+    I_s, I_g = oracle_index.build_index_trie(b.tok, b.cu_seqlens)
+    rng = np.random.default_rng(8)
+    h_c = rng.standard_normal((len(I_g), 7))
+    h = h_c[I_s]                                  # rows of duplicates are copies
+    w = rng.standard_normal((11, 7))
+    y_c = orc.lm_head_logits(h, w, rows=I_g)
+    np.testing.assert_array_equal(y_c[I_s], orc.lm_head_logits(h, w))
