@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--sweep-model", choices=["0.6B", "4B", "8B"], default="0.6B", help="--workload SWEEP: model shape")
     ap.add_argument("--sweep-prefix", type=int, default=2048, help="--workload SWEEP: shared prefix length")
     ap.add_argument("--sweep-suffix", type=int, default=256, help="--workload SWEEP: suffix length")
+    ap.add_argument("--lm-head", action="store_true",
+                    help="also time the LM head (tied to the embedding) on the last token of every sequence, outside "
+                         "the timed steps; reported as lm_head_last_token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough budget of the oracle timing")
     args = ap.parse_args()
@@ -88,6 +91,9 @@ def main() -> int:
     if split:
         import dataclasses
         weights = synth.SynthWeights(dataclasses.replace(weights.cfg, split_norm_out=split), weights.seed)
+    if args.lm_head:
+        import dataclasses
+        weights = synth.SynthWeights(dataclasses.replace(weights.cfg, lm_head=1), weights.seed)
     cfg = weights.cfg
     model = harness.upload_model(weights)
     run = harness.Runner(model, batch.N, batch.B)
@@ -211,6 +217,16 @@ def main() -> int:
                      "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom,
                      "executed_flops_per_launch": flops_dom * (2 if cfg.split_norm_out == 1 else 1)},
     }
+
+    if args.lm_head:
+        last = (cu[1:] - 1).to(torch.int32).contiguous()
+        ws_head = binding.alloc_workspace(binding.radix_lm_head_workspace_bytes(model, B))
+        logits = torch.empty((B, cfg.vocab), dtype=torch.float32, device="cuda")
+        t_head = timed(lambda: binding.radix_lm_head(model, out, last, ws_head, out=logits), max(k2, 10))
+        w_bytes = cfg.vocab * d * (2 if cfg.dtype != "f32" else 4)
+        result["lm_head_last_token"] = {"rows": B, "vocab": cfg.vocab, "ms": t_head,
+                                        "weight_GBps": w_bytes / (t_head * 1e-3) / 1e9,
+                                        "tflops": 2.0 * B * cfg.vocab * d / (t_head * 1e-3) / 1e12}
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(batch, weights, args.cpu_seconds)

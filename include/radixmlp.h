@@ -40,7 +40,7 @@ typedef enum radix_status {
     RADIX_ERR_WORKSPACE_TOO_SMALL = -4,
     RADIX_ERR_MISALIGNED = -5,        /* pointer not aligned as documented */
     RADIX_ERR_BAD_CU_SEQLENS = -6,    /* device data: cu_seqlens[0] != 0, decreasing, or last != N */
-    RADIX_ERR_BAD_TOKEN = -7,         /* device data: token id < 0 or >= vocab, or position id out of range */
+    RADIX_ERR_BAD_TOKEN = -7,         /* device data: token id < 0 or >= vocab, position id or row index out of range */
     RADIX_ERR_HIP = -8,               /* a HIP runtime call failed */
     RADIX_ERR_BAD_CONFIG = -9         /* inconsistent model configuration */
 } radix_status;
@@ -70,6 +70,10 @@ typedef struct radix_model_config {
                               error, for twice the work in that GEMM.  1: both norms of a layer (Q/K/V and gate/up
                               GEMMs doubled); 2: the pre-attention norm only (Q/K/V GEMM doubled).  For deep, wide
                               random-init models whose layers amplify perturbations. */
+    int32_t lm_head;     /* 0: no LM head (radix_lm_head returns RADIX_ERR_UNSUPPORTED); 1: head tied to the embedding
+                            matrix; 2: separate matrix radix_weights.lm_head.  Non-zero makes radix_model_create
+                            keep the head in the operand type (a converted copy of the embedding when that
+                            differs from the weight type).  16-bit operand types need vocab % 128 == 0. */
     float eps;           /* RMSNorm epsilon (inside the square root) */
     float rope_base;
 } radix_model_config;
@@ -94,6 +98,7 @@ typedef struct radix_weights {
     const void* embed;                       /* [vocab, d] in config.dtype (device) */
     const float* gf;                         /* [d] final norm gain (device) */
     const radix_layer_weights* layers_host;  /* HOST array of n_layers structs of device pointers */
+    const void* lm_head;                     /* [vocab, d] in config.dtype (device); read only when config.lm_head == 2 */
 } radix_weights;
 
 typedef struct radix_model radix_model;      /* opaque */
@@ -187,6 +192,26 @@ int radix_prefill_forward(const radix_model* model, const int32_t* tok, const in
 int radix_prefill_forward_nodedup(const radix_model* model, const int32_t* tok, const int32_t* pos,
                                   const int32_t* cu_seqlens, int32_t B, int32_t N, int32_t max_seqlen,
                                   float* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * radix_lm_head - logits of selected rows (paper: Algorithm 1, output block, "logits = LMHead(h)"; a
+ * bias-free linear map, tied to the embedding or a matrix of its own, see radix_model_config.lm_head).
+ *   hidden    [n_src_rows, d] fp32: final-norm hidden states, i.e. what radix_prefill_forward wrote.
+ *   rows      [n_rows] int32 row indices into hidden, or NULL for rows 0 .. n_rows-1 (n_rows <= n_src_rows).
+ *             E.g. cu_seqlens[b+1]-1 for the last token of every sequence (a reranker's output), or
+ *             I_gather for logits in compact space, which radix_index_select_rows with I_scatter then
+ *             expands to all N rows (Algorithm 1: "y_c = LMHead(h), y = Scatter(y_c)").  An index outside
+ *             [0, n_src_rows) is clamped and recorded as RADIX_ERR_BAD_TOKEN in the workspace status word.
+ *   logits    [n_rows, vocab] fp32, 16-byte aligned.
+ *   ws        at least radix_lm_head_workspace_bytes(model, n_rows) bytes, 256-byte aligned; may be the
+ *             forward's workspace when that is large enough (the status word is shared, the rest reused).
+ * Rows are converted to the operand type (one rounding for 16-bit operands), multiplied with fp32
+ * accumulation in a fixed order (a row's logits do not depend on which other rows are selected).
+ * Asynchronous on `stream`.
+ */
+int radix_lm_head_workspace_bytes(const radix_model* model, int32_t max_rows, size_t* bytes_out);
+int radix_lm_head(const radix_model* model, const float* hidden, int32_t n_src_rows, const int32_t* rows,
+                  int32_t n_rows, float* logits, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * radix_index_select_rows - the gather/scatter operator itself (paper: Implementation Details,

@@ -21,6 +21,7 @@ _DTYPES = {"f32": RADIX_F32, "bf16": RADIX_BF16, "f16": RADIX_F16}
 EXPORTS = (
     "radix_model_create", "radix_model_destroy", "radix_index_workspace_bytes", "radix_workspace_bytes",
     "radix_build_index", "radix_prefill_forward", "radix_prefill_forward_nodedup",
+    "radix_lm_head_workspace_bytes", "radix_lm_head",
     "radix_index_select_rows", "radix_device_status", "radix_status_string",
     "radix_timing_enable", "radix_timing_collect",
 )
@@ -37,7 +38,7 @@ class RadixError(RuntimeError):
 
 class radix_model_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d", "n_q_heads", "n_kv_heads", "head_dim", "d_int", "vocab",
-                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "split_norm_out")] + [("eps", C.c_float), ("rope_base", C.c_float)]
+                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "split_norm_out", "lm_head")] + [("eps", C.c_float), ("rope_base", C.c_float)]
 
 
 class radix_layer_weights(C.Structure):
@@ -45,7 +46,8 @@ class radix_layer_weights(C.Structure):
 
 
 class radix_weights(C.Structure):
-    _fields_ = [("embed", C.c_void_p), ("gf", C.c_void_p), ("layers_host", C.POINTER(radix_layer_weights))]
+    _fields_ = [("embed", C.c_void_p), ("gf", C.c_void_p), ("layers_host", C.POINTER(radix_layer_weights)),
+                ("lm_head", C.c_void_p)]
 
 
 class radix_fwd_opts(C.Structure):
@@ -73,6 +75,8 @@ def _lib() -> C.CDLL:
                                               vp, vp, sz, vp]
         lib.radix_prefill_forward_nodedup.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
         lib.radix_index_select_rows.argtypes = [vp, i32, vp, i32, sz, vp, vp, vp]
+        lib.radix_lm_head_workspace_bytes.argtypes = [vp, i32, C.POINTER(sz)]
+        lib.radix_lm_head.argtypes = [vp, vp, i32, vp, i32, vp, vp, sz, vp]
         lib.radix_device_status.argtypes = [vp, sz, vp]
         lib.radix_timing_enable.argtypes = [C.c_uint32, C.c_uint32]
         lib.radix_timing_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
@@ -134,19 +138,20 @@ def make_config(cfg: Any) -> radix_model_config:
     compute = getattr(cfg, "compute_dtype", None) or cfg.dtype
     return radix_model_config(cfg.n_layers, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_int, cfg.vocab,
                               cfg.max_pos, int(cfg.qk_norm), _DTYPES[cfg.dtype], _DTYPES[compute],
-                              int(getattr(cfg, "split_norm_out", 0)), cfg.eps, cfg.rope_base)
+                              int(getattr(cfg, "split_norm_out", 0)), int(getattr(cfg, "lm_head", 0)), cfg.eps,
+                              cfg.rope_base)
 
 
 def radix_model_create(cfg: Any, embed: torch.Tensor, gf: torch.Tensor,
-                       layers: Sequence[Mapping[str, torch.Tensor]]) -> Model:
-    """embed/gf/layers: CUDA tensors ([out, in] matrices in the config dtype, fp32 gains)."""
+                       layers: Sequence[Mapping[str, torch.Tensor]], lm_head: Optional[torch.Tensor] = None) -> Model:
+    """embed/gf/layers/lm_head: CUDA tensors ([out, in] matrices in the config dtype, fp32 gains)."""
     c = make_config(cfg)
     arr = (radix_layer_weights * len(layers))()
     for l, lw in enumerate(layers):
         for name, _ in radix_layer_weights._fields_:
             t = lw.get(name)
             setattr(arr[l], name, None if t is None else t.data_ptr())
-    w = radix_weights(embed.data_ptr(), gf.data_ptr(), arr)
+    w = radix_weights(embed.data_ptr(), gf.data_ptr(), arr, _ptr(lm_head))
     out = C.c_void_p()
     _check(_lib().radix_model_create(C.byref(c), C.byref(w), C.byref(out)), "radix_model_create")
     return Model(out.value, c)
@@ -216,6 +221,28 @@ def radix_prefill_forward_nodedup(model: Model, tok: torch.Tensor, pos: Optional
     rc = _lib().radix_prefill_forward_nodedup(model.handle, _ptr(tok), _ptr(pos), _ptr(cu_seqlens), B, N, max_seqlen,
                                               _ptr(out), _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "radix_prefill_forward_nodedup")
+    return out
+
+
+def radix_lm_head_workspace_bytes(model: Model, max_rows: int) -> int:
+    n = C.c_size_t()
+    _check(_lib().radix_lm_head_workspace_bytes(model.handle, max_rows, C.byref(n)), "radix_lm_head_workspace_bytes")
+    return n.value
+
+
+def radix_lm_head(model: Model, hidden: torch.Tensor, rows: Optional[torch.Tensor], ws: torch.Tensor,
+                  out: Optional[torch.Tensor] = None, n_rows: Optional[int] = None,
+                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """logits[n_rows, vocab] (fp32) of hidden[rows] (or of the first n_rows rows when rows is None)."""
+    if hidden.dtype != torch.float32 or not hidden.is_contiguous():
+        raise TypeError("hidden must be a contiguous fp32 tensor")
+    n_src = hidden.shape[0]
+    n = rows.numel() if rows is not None else (n_src if n_rows is None else n_rows)
+    if out is None:
+        out = torch.empty((n, model.cfg.vocab), dtype=torch.float32, device=hidden.device)
+    rc = _lib().radix_lm_head(model.handle, _ptr(hidden), n_src, None if rows is None else _ptr(_i32(rows, "rows")), n,
+                              _ptr(out), _ptr(ws), ws.numel(), _stream(stream))
+    _check(rc, "radix_lm_head")
     return out
 
 

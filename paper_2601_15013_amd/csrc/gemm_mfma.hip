@@ -423,8 +423,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     const int lane = lane_opaque;
     const int r = lane & 31, g = lane >> 5;
 
-    if (EPI == EPI_RESIDUAL) {
-        // fp32 read-modify-write of the residual stream straight from the accumulator layout: per
+    if (EPI == EPI_RESIDUAL || EPI == EPI_STORE_F32) {
+        // fp32 read-modify-write of the residual stream (or a plain fp32 store) straight from the accumulator layout: per
         // instruction 32 rows x 32 contiguous bytes; all loads of a row block are issued before its
         // stores, and nothing has to be converted, so the LDS detour does not pay here.
 #pragma unroll
@@ -437,7 +437,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     f32x4* p = reinterpret_cast<f32x4*>(orow + j * 32 + 8 * q + 4 * g);
-                    f32x4 v = *p;
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (EPI == EPI_RESIDUAL) v = *p;
 #pragma unroll
                     for (int t = 0; t < 4; ++t) v[t] += acc[j][i][q * 4 + t];
                     *p = v;
@@ -558,6 +559,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
     else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
     else if (epilogue == EPI_SWIGLU) RADIX_LAUNCH(EPI_SWIGLU);
+    else if (epilogue == EPI_STORE_F32) RADIX_LAUNCH(EPI_STORE_F32);
     else if (epilogue == EPI_QKV_ROPE) {
         if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_QKV_ROPE);
         else return RADIX_ERR_UNSUPPORTED;

@@ -35,6 +35,11 @@ void launch_qknorm_rope(void* qkv, int dtype, int M, int n_q_heads, int n_kv_hea
                         const float* gq, const float* gk, float eps, const int32_t* pos_c,
                         const float* cos_tab, const float* sin_tab, hipStream_t stream);
 
+// out[r, :] = (operand type) src[sel ? sel[r] : r, :] for r < n_rows; src is fp32 [n_src, d].  out_dtype RADIX_F32
+// copies.  Entries of sel outside [0, n_src) are clamped and reported in *status.
+void launch_rows_to_operand(const float* src, int n_src, const int32_t* sel, int n_rows, int d, void* out,
+                            int out_dtype, int32_t* status, hipStream_t stream);
+
 // dst[i] = (f16) src[i] for n bf16 values (weights handed over as bf16, multiplied as fp16)
 void launch_bf16_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t stream);
 
@@ -43,7 +48,8 @@ enum GemmEpilogue {
     EPI_STORE = 0,     // C stored in the activation dtype
     EPI_RESIDUAL = 1,  // resid[M, Nout] (fp32) += C
     EPI_SWIGLU = 2,    // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
-    EPI_QKV_ROPE = 3   // EPI_STORE of the fused q|k|v row with per-head RMSNorm and RoPE applied to q and k heads
+    EPI_QKV_ROPE = 3,  // EPI_STORE of the fused q|k|v row with per-head RMSNorm and RoPE applied to q and k heads
+    EPI_STORE_F32 = 4  // C stored as fp32 (16-bit operand GEMMs only; the fp32 GEMM's EPI_STORE already is fp32)
 };
 // Extra inputs of EPI_QKV_ROPE (head_dim 128): gains and tables are device pointers.
 struct QkvEpilogue {

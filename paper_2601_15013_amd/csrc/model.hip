@@ -19,6 +19,7 @@ struct radix_model {
     radix_model_config cfg;
     char* blob = nullptr;          // one device allocation holding everything below
     const void* embed = nullptr;
+    const void* lm_head = nullptr;  // [vocab, d] in the operand type (may alias embed), or null
     const float* gf = nullptr;
     const float* cos_tab = nullptr;
     const float* sin_tab = nullptr;
@@ -115,6 +116,8 @@ int check_config(const radix_model_config& c) {
     if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
     if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
     if (c.split_norm_out < 0 || c.split_norm_out > 2) return RADIX_ERR_BAD_CONFIG;
+    if (c.lm_head < 0 || c.lm_head > 2) return RADIX_ERR_BAD_CONFIG;
+    if (c.lm_head && c.dtype == RADIX_BF16 && (c.vocab % 128 != 0)) return RADIX_ERR_UNSUPPORTED;
     if (c.split_norm_out && (c.dtype != RADIX_BF16 || c.d % 256 != 0)) return RADIX_ERR_UNSUPPORTED;
     if (c.dtype == RADIX_BF16) {
         // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 32 and every
@@ -136,6 +139,7 @@ extern "C" int radix_model_create(const radix_model_config* config, const radix_
     int rc = check_config(c);
     if (rc != RADIX_OK) return rc;
     if (!weights->embed || !weights->gf || !weights->layers_host) return RADIX_ERR_NULL_POINTER;
+    if (c.lm_head == 2 && !weights->lm_head) return RADIX_ERR_NULL_POINTER;
     for (int l = 0; l < c.n_layers; ++l) {
         const radix_layer_weights& w = weights->layers_host[l];
         if (!w.g1 || !w.wq || !w.wk || !w.wv || !w.wo || !w.g2 || !w.wg || !w.wu || !w.wd) return RADIX_ERR_NULL_POINTER;
@@ -148,6 +152,10 @@ extern "C" int radix_model_create(const radix_model_config* config, const radix_
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
     const size_t o_embed = take((size_t)c.vocab * d * es), o_gf = take(d * 4);
+    // the head needs a copy of its own unless it is the embedding matrix and that already has the operand type
+    const bool head_converted = c.dtype == RADIX_BF16 && c.compute_dtype == RADIX_F16;
+    const bool head_copy = c.lm_head == 2 || (c.lm_head == 1 && head_converted);
+    const size_t o_head = head_copy ? take((size_t)c.vocab * d * es) : 0;
     const size_t o_cos = take((size_t)c.max_pos * half * 4), o_sin = take((size_t)c.max_pos * half * 4);
     struct LO { size_t g1, g2, gq, gk, wqkv, wo, wgu, wd; };
     std::vector<LO> lo(c.n_layers);
@@ -183,6 +191,16 @@ extern "C" int radix_model_create(const radix_model_config* config, const radix_
         if (hipMemcpy(b + o_sin, st.data(), st.size() * 4, hipMemcpyHostToDevice) != hipSuccess) ok = false;
     }
     m->embed = b + o_embed;
+    if (c.lm_head) {
+        if (head_copy) {
+            d2d(o_head, c.lm_head == 2 ? weights->lm_head : weights->embed, (size_t)c.vocab * d * es);
+            if (head_converted)
+                launch_bf16_to_f16((const bf16_t*)(b + o_head), (f16_t*)(b + o_head), (size_t)c.vocab * d, 0);
+            m->lm_head = b + o_head;
+        } else {
+            m->lm_head = b + o_embed;
+        }
+    }
     m->gf = (const float*)(b + o_gf);
     m->cos_tab = (const float*)(b + o_cos);
     m->sin_tab = (const float*)(b + o_sin);
@@ -423,6 +441,43 @@ extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int
     if (rc != RADIX_OK) return rc;
     return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, false, out, ws,
                         ws_bytes, (hipStream_t)stream);
+}
+
+extern "C" int radix_lm_head_workspace_bytes(const radix_model* model, int32_t max_rows, size_t* bytes_out) {
+    if (!model || !bytes_out) return RADIX_ERR_NULL_POINTER;
+    if (max_rows < 0) return RADIX_ERR_BAD_SIZE;
+    *bytes_out = RADIX_WS_HEADER_BYTES + align_up((size_t)(max_rows ? max_rows : 1) * model->cfg.d * esize(model->cfg.compute_dtype), 256);
+    return RADIX_OK;
+}
+
+extern "C" int radix_lm_head(const radix_model* model, const float* hidden, int32_t n_src_rows, const int32_t* rows,
+                             int32_t n_rows, float* logits, void* ws, size_t ws_bytes, void* stream_) {
+    if (!model || !ws) return RADIX_ERR_NULL_POINTER;
+    if (n_src_rows < 0 || n_rows < 0) return RADIX_ERR_BAD_SIZE;
+    if (!rows && n_rows > n_src_rows) return RADIX_ERR_BAD_SIZE;
+    if (!model->lm_head) return RADIX_ERR_UNSUPPORTED;
+    const radix_model_config& c = model->cfg;
+    size_t need = 0;
+    radix_lm_head_workspace_bytes(model, n_rows, &need);
+    if (ws_bytes < need) return RADIX_ERR_WORKSPACE_TOO_SMALL;
+    if ((((uintptr_t)ws) & 255) != 0 || (((uintptr_t)logits) & 15) != 0) return RADIX_ERR_MISALIGNED;
+    hipStream_t stream = (hipStream_t)stream_;
+    int32_t* hdr = (int32_t*)ws;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(1), 0, stream, hdr);
+    if (n_rows == 0) { HIP_TRY(hipGetLastError()); return RADIX_OK; }
+    if (!hidden || !logits) return RADIX_ERR_NULL_POINTER;
+    if (n_src_rows == 0) return RADIX_ERR_BAD_SIZE;
+    void* a = (char*)ws + RADIX_WS_HEADER_BYTES;
+    const int dt = c.compute_dtype;
+    launch_rows_to_operand(hidden, n_src_rows, rows, n_rows, c.d, a, dt, hdr, stream);
+    if (dt == RADIX_F32) {
+        launch_gemm_f32((const float*)a, (const float*)model->lm_head, n_rows, c.vocab, c.d, EPI_STORE, logits, stream);
+    } else {
+        const int rc = launch_gemm_mfma(a, model->lm_head, n_rows, c.vocab, c.d, EPI_STORE_F32, logits, dt, 0, stream);
+        if (rc != RADIX_OK) return rc;
+    }
+    HIP_TRY(hipGetLastError());
+    return RADIX_OK;
 }
 
 extern "C" int radix_timing_enable(uint32_t category_mask, uint32_t every_nth) {

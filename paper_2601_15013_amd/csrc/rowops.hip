@@ -219,6 +219,35 @@ void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* id
     }
 }
 
+// Row selection + conversion in front of the LM head: one wavefront per output row.
+template <typename T>
+__global__ void rows_to_operand_kernel(const float* __restrict__ src, int n_src, const int32_t* __restrict__ sel,
+                                       int n_rows, int d, T* __restrict__ out, int32_t* __restrict__ status) {
+    const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= n_rows) return;
+    int s = sel ? sel[row] : row;
+    if (s < 0 || s >= n_src) {
+        if (lane == 0) set_status(status, RADIX_ERR_BAD_TOKEN);
+        s = s < 0 ? 0 : n_src - 1;
+    }
+    const float* sp = src + (size_t)s * d;
+    T* dp = out + (size_t)row * d;
+    for (int c = lane; c < d; c += 64) dp[c] = from_f32<T>(sp[c]);
+}
+
+void launch_rows_to_operand(const float* src, int n_src, const int32_t* sel, int n_rows, int d, void* out,
+                            int out_dtype, int32_t* status, hipStream_t stream) {
+    if (n_rows <= 0 || n_src <= 0) return;
+    const dim3 grid(ceil_div(n_rows, 4)), block(256);
+    if (out_dtype == RADIX_F32)
+        hipLaunchKernelGGL(rows_to_operand_kernel<float>, grid, block, 0, stream, src, n_src, sel, n_rows, d, (float*)out, status);
+    else if (out_dtype == RADIX_BF16)
+        hipLaunchKernelGGL(rows_to_operand_kernel<bf16_t>, grid, block, 0, stream, src, n_src, sel, n_rows, d, (bf16_t*)out, status);
+    else
+        hipLaunchKernelGGL(rows_to_operand_kernel<f16_t>, grid, block, 0, stream, src, n_src, sel, n_rows, d, (f16_t*)out, status);
+}
+
 // First representative position of every sequence: the smallest p with I_gather[I_scatter[start + p]] ==
 // start + p, or len if the whole sequence duplicates earlier ones.  In a trie the predicate is monotone
 // along a sequence (a token that opens a new node makes every later token of the sequence open one

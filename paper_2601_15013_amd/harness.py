@@ -14,7 +14,7 @@ def _to_dev(a: np.ndarray, dtype: torch.dtype, device: str) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).to(device)
 
 
-def upload_model(weights: synth.SynthWeights, device: str = "cuda") -> binding.Model:
+def upload_model(weights: synth.SynthWeights, device: str = "cuda", lm_head=None) -> binding.Model:
     """Generate the weights layer by layer, copy them to the GPU and create the library model
     (which keeps its own re-packed copy, so the uploaded tensors are released afterwards)."""
     cfg = weights.cfg
@@ -25,7 +25,8 @@ def upload_model(weights: synth.SynthWeights, device: str = "cuda") -> binding.M
     for l in range(cfg.n_layers):
         lw = weights.layer(l)
         layers.append({k: _to_dev(v, torch.float32 if k.startswith("g") else mt, device) for k, v in lw.items()})
-    model = binding.radix_model_create(cfg, embed, gf, layers)
+    head = None if lm_head is None else _to_dev(lm_head, mt, device)      # only read when cfg.lm_head == 2
+    model = binding.radix_model_create(cfg, embed, gf, layers, lm_head=head)
     torch.cuda.synchronize()
     return model
 

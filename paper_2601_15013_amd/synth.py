@@ -43,6 +43,7 @@ class ModelConfig:
     qk_norm: bool = True
     max_pos: int = 4096
     compute_dtype: str = ""   # operand type of the GPU path: "" = default ("f32", or "f16" for bf16 weights)
+    lm_head: int = 0         # GPU path: 0 no LM head, 1 tied to the embedding, 2 separate matrix (see radixmlp.h)
     split_norm_out: int = 0  # GPU path: carry RMSNorm outputs as (hi, lo) pairs: 1 both norms, 2 pre-attention only (see radixmlp.h)
 
     def __post_init__(self):

@@ -73,9 +73,9 @@ def test_forward_rejects_bad_host_arguments(lib):
 def test_model_create_rejects_bad_config(lib):
     out = C.c_void_p()
     assert lib.radix_model_create(None, None, C.byref(out)) == -1
-    w = binding.radix_weights(0x1000, 0x1000, None)
+    w = binding.radix_weights(0x1000, 0x1000, None, None)
     good = dict(n_layers=1, d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_int=768, vocab=10, max_pos=16,
-                qk_norm=1, dtype=0, compute_dtype=0, split_norm_out=0, eps=1e-6, rope_base=1e6)
+                qk_norm=1, dtype=0, compute_dtype=0, split_norm_out=0, lm_head=0, eps=1e-6, rope_base=1e6)
 
     def create(**kw):
         c = binding.radix_model_config(**dict(good, **kw))
@@ -90,10 +90,19 @@ def test_model_create_rejects_bad_config(lib):
     assert create(split_norm_out=1) == -3        # hi/lo activations exist for 16-bit operands only
     assert create(split_norm_out=2) == -3
     assert create(split_norm_out=5) == -9
+    assert create(lm_head=3) == -9
+    assert create(dtype=1, compute_dtype=2, head_dim=128, n_q_heads=2, n_kv_heads=1, d=256, d_int=512, vocab=1000, lm_head=1) == -3   # 16-bit head: vocab % 128
     assert create(dtype=1, compute_dtype=0, head_dim=128) == -3
     assert create(d_int=100) == -3               # gate/up interleave needs multiples of 32
     assert create() == -1                        # config fine, layers_host NULL
     assert out.value is None
+
+
+def test_lm_head_rejects_bad_host_arguments(lib):
+    fake = C.c_void_p(0x1000)
+    n = C.c_size_t()
+    assert lib.radix_lm_head_workspace_bytes(None, 4, C.byref(n)) == -1
+    assert lib.radix_lm_head(None, fake, 4, None, 4, fake, fake, 1 << 20, None) == -1      # model NULL
 
 
 def test_index_select_rejects_bad_host_arguments(lib):
