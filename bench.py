@@ -6,7 +6,8 @@ HBM: radix_build_index (trie index maps, including its one 8-byte device-to-host
 followed by radix_prefill_forward (compact-space position-wise ops + full-layout attention).
 The headline value is uncompressed tokens per second, N / step time.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: metric, value (tokens/s), ms_per_step, config, the roofline of the dominant kernel,
+the CPU oracle baseline and context fields (per-kernel times, speedup over the no-dedup path).
 """
 import argparse
 import json

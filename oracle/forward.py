@@ -21,7 +21,7 @@ What is computed, per sequence with tokens t_0..t_{n-1} and positions p_i (defau
       x  += Wd ( silu(Wg b) * (Wu b) )                      SwiGLU MLP, Background Eq. 5
   y_i = RMSNorm(x_i; gf)                                    final norm (Algorithm 1, "Output")
 
-Readings where the paper is silent (all listed in DESIGN.md): the paper's "LayerNorm" is
+Readings where the paper is silent: the paper's "LayerNorm" is
 RMSNorm x * rsqrt(mean(x^2) + eps) * g with eps inside the square root; RoPE pairs element i
 with i + hd/2, angle p * base^(-2i/hd); softmax scale 1/sqrt(hd); silu(z) = z / (1 + exp(-z));
 the output is the final-norm hidden state; ``lm_head_logits`` is Algorithm 1's tail (logits = LMHead(h)) for
