@@ -112,3 +112,12 @@ def test_index_select_rejects_bad_host_arguments(lib):
     assert f(None, 4, fake, 2, 16, fake, None, None) == -1
     assert f(fake, 4, fake, 2, 6, fake, None, None) == -5      # row_bytes not a multiple of 4
     assert f(fake, 4, fake, 0, 16, fake, None, None) == 0      # nothing to do
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode == 2
+    assert "ONE GPU" in p.stderr and p.stdout.strip() == ""
