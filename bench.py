@@ -23,7 +23,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 
 # HBM-side bytes per gate/up GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled
 # by the 256 MiB copy dispatch of the same run (profiles/gemm_gateup_C2_hbm_traffic.md); None where not measured.
-GATEUP_TRAFFIC_BYTES = {"C2": int(82646 * 1024 * 1.984 + 47202 * 1024)}
+GATEUP_TRAFFIC_BYTES = {"C2": int(82653 * 1024 * 1.984 + 47202 * 1024)}
 
 WORKLOAD_TEXT = {
     "C1": "C1: tiny Qwen3-style decoder fp32, 8 seqs = 32 shared + 16 own tokens",
