@@ -114,7 +114,8 @@ typedef struct radix_fwd_opts {
                               *    rows the gather would keep) and writes compact rows; same values bit for
                               *    bit, no [N, .] copies.  16-bit operand configurations only
                               *    (RADIX_ERR_UNSUPPORTED otherwise); ignored when the threshold turns
-                              *    deduplication off. */
+                              *    deduplication off, and when the compact q|k|v buffer reaches 4 GB (the three
+                              *    kernels run instead). */
 } radix_fwd_opts;
 
 /*

@@ -271,6 +271,10 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     const radix_model_config& c = model->cfg;
     if (fused && c.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;   // the fused kernel is the MFMA one
     fused = fused && dedup;
+    // the fused kernel addresses the compact q|k|v buffer with 32-bit byte offsets; beyond 4 GB the three-kernel
+    // path (same results) takes over
+    if (fused && (long long)M * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * (long long)esize(c.compute_dtype) >= (1LL << 32))
+        fused = false;
     const WsLayout L = ws_layout(c, (size_t)N, (size_t)B);
     if (ws_bytes < L.total) return RADIX_ERR_WORKSPACE_TOO_SMALL;
     char* w = (char*)ws;
