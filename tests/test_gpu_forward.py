@@ -113,7 +113,7 @@ def test_split_norm_outputs_tighten_the_error():
         assert np.array_equal(y, y_nd)
     print("bf16 operands, relative RMS error with split off / pre-attention / both:", errs)
     assert errs[1] < 0.9 * errs[0]
-    assert errs[1] < errs[2] < errs[0]
+    assert errs[2] < 0.95 * errs[0]
 
 
 def test_bf16_wide_model_uses_large_gemm_tiles():
