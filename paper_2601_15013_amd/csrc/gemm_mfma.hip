@@ -11,12 +11,15 @@
 //   * Workgroup tile BM x BN, k-tile 32, 256 threads = 4 wavefronts in a WAVES_M x WAVES_N grid;
 //     each wavefront owns (BM/WAVES_M) x (BN/WAVES_N) outputs as 32x32 MFMA accumulators.
 //   * The product is formed transposed, C^T = W * A^T (weights are the MFMA "A" operand), so a
-//     lane owns one output ROW and 4 consecutive columns per register quad: epilogue stores are
-//     8 bytes (16-bit out) or 16 bytes (fp32 residual read-modify-write) per lane.
+//     lane owns one output ROW and 4 consecutive columns per register quad: the fp32 epilogues
+//     (residual read-modify-write, plain fp32 store) access 16 bytes per lane straight from that
+//     layout, the 16-bit ones transpose through LDS and store whole 256-byte row segments.
 //   * Global -> LDS goes through global_load_lds_dwordx4 (no VGPR staging): a wavefront fills
 //     1 KB of LDS per instruction, lane L landing at byte 16 L; the XOR swizzle that keeps the
 //     fragment reads bank-conflict free is therefore applied to the GLOBAL address each lane
-//     fetches.  Four LDS stages, one barrier per k-tile, loads issued three tiles ahead.  The
+//     fetches.  K-tiles travel in pairs through a ring of five or six LDS stages (the two 64-byte
+//     halves of a 128-byte line are requested back to back), one barrier per pair, loads spread
+//     one per MFMA slice over the pair; details at the main loop.  The
 //     load is issued from inline assembly: issued through the compiler builtin, the compiler's
 //     wait-count pass makes every later LDS read wait for ALL loads in flight (it cannot prove
 //     that the reads of one stage do not alias the fills of the others), which serialises the
