@@ -116,6 +116,11 @@ typedef struct radix_fwd_opts {
                               *    (RADIX_ERR_UNSUPPORTED otherwise); ignored when the threshold turns
                               *    deduplication off, and when the compact q|k|v buffer reaches 4 GB (the three
                               *    kernels run instead). */
+    int32_t pad_compact_to;  /* 0 or 1: off.  k > 1: the compact space is rounded up to a multiple of k rows (never
+                              *    beyond N) with copies of the first representative, whose results are discarded
+                              *    (paper: Implementation Details, performance padding): the position-wise kernels
+                              *    then see one of few row counts, e.g. for graph capture per bucket.  Outputs are
+                              *    unchanged bit for bit. */
 } radix_fwd_opts;
 
 /*

@@ -51,7 +51,8 @@ class radix_weights(C.Structure):
 
 
 class radix_fwd_opts(C.Structure):
-    _fields_ = [("threshold", C.c_float), ("force_dedup", C.c_int32), ("fused_attention", C.c_int32)]
+    _fields_ = [("threshold", C.c_float), ("force_dedup", C.c_int32), ("fused_attention", C.c_int32),
+                ("pad_compact_to", C.c_int32)]
 
 
 _LIB: Optional[C.CDLL] = None
@@ -199,11 +200,11 @@ def radix_prefill_forward(model: Model, tok: torch.Tensor, pos: Optional[torch.T
                           max_seqlen: int, I_scatter: torch.Tensor, I_gather: torch.Tensor, n_compact: int,
                           ws: torch.Tensor, out: Optional[torch.Tensor] = None, threshold: float = 1.0,
                           force_dedup: bool = False, stream: Optional[torch.cuda.Stream] = None,
-                          fused_attention: bool = False) -> torch.Tensor:
+                          fused_attention: bool = False, pad_compact_to: int = 0) -> torch.Tensor:
     N, B = tok.numel(), cu_seqlens.numel() - 1
     if out is None:
         out = torch.empty((N, model.cfg.d), dtype=torch.float32, device=cu_seqlens.device)
-    opts = radix_fwd_opts(threshold, int(force_dedup), int(fused_attention))
+    opts = radix_fwd_opts(threshold, int(force_dedup), int(fused_attention), int(pad_compact_to))
     rc = _lib().radix_prefill_forward(model.handle, _ptr(tok), _ptr(pos), _ptr(cu_seqlens), B, N, max_seqlen,
                                       _ptr(I_scatter), _ptr(I_gather), n_compact, C.byref(opts), _ptr(out),
                                       _ptr(ws), ws.numel(), _stream(stream))

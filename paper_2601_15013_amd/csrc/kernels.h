@@ -9,16 +9,18 @@
 size_t radix_index_ws_bytes(int B);
 
 // ---- row operations (rowops.hip)
-// dst[r, :] = src[idx[r], :]; row_bytes % 4 == 0.  idx == nullptr copies rows 1:1.
+// dst[r, :] = src[idx[r], :]; row_bytes % 4 == 0.  idx == nullptr copies rows 1:1.  Rows r >= n_idx (n_idx < 0:
+// none) take source row 0: the padding rows of a compact space rounded up to a bucket.
 void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* idx, int n_rows,
-                              size_t row_bytes, void* dst, int32_t* status, hipStream_t stream);
+                              size_t row_bytes, void* dst, int32_t* status, hipStream_t stream, int n_idx = -1);
 // Records RADIX_ERR_BAD_CU_SEQLENS in *status when cu is not 0 .. N non-decreasing with every
 // sequence <= max_seqlen.  (Kernels that index through cu clamp what they read from it.)
 void launch_validate_cu(const int32_t* cu, int B, int N, int max_seqlen, int32_t* status, hipStream_t stream);
 // pos_full[i] = i - cu[seq(i)]
 void launch_default_positions(const int32_t* cu, int B, int N, int32_t* pos_full, hipStream_t stream);
-// ids_c[j] = tok[Ig[j]], pos_c[j] = pos[Ig[j]]   (Ig == nullptr: identity)
-void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* Ig, int M, int N,
+// ids_c[j] = tok[Ig[j]], pos_c[j] = pos[Ig[j]] for j < M_valid (Ig == nullptr: identity); rows M_valid <= j < M are
+// padding: copies of token 0
+void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* Ig, int M, int M_valid, int N,
                         int vocab, int max_pos, int32_t* ids_c, int32_t* pos_c, int32_t* status,
                         hipStream_t stream);
 // h[j, :] = (float) E[ids_c[j], :]

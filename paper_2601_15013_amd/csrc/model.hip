@@ -266,8 +266,8 @@ extern "C" int radix_device_status(void* ws, size_t ws_bytes, void* stream) {
 namespace {
 
 int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* pos, const int32_t* cu, int B, int N,
-                 int max_seqlen, const int32_t* Is, const int32_t* Ig, int M, bool dedup, bool fused, float* out,
-                 void* ws, size_t ws_bytes, hipStream_t stream) {
+                 int max_seqlen, const int32_t* Is, const int32_t* Ig, int M, bool dedup, bool fused, int pad_to,
+                 float* out, void* ws, size_t ws_bytes, hipStream_t stream) {
     const radix_model_config& c = model->cfg;
     if (fused && c.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;   // the fused kernel is the MFMA one
     fused = fused && dedup;
@@ -299,14 +299,24 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     void* mlp = w + L.mlp;
     float* ynorm = (float*)(w + L.ynorm);
 
+    // Performance padding (paper: Implementation Details): the compact space is rounded up to a multiple of
+    // pad_to with copies of the first representative, as far as the N rows the workspace holds allow; the
+    // padding rows are computed and never scattered.  M_valid = N' keeps indexing the maps.
+    const int M_valid = M;
+    if (dedup && pad_to > 1) {
+        const long long padded = ((long long)M + pad_to - 1) / pad_to * pad_to;
+        M = (int)(padded < (long long)N ? padded : (long long)N);
+        if (M < M_valid) M = M_valid;
+    }
+
     // Token compaction: positions and ids of the representatives (Algorithm 1, first block)
     if (!pos) {
         launch_default_positions(cu, B, N, pos_full, stream);
         pos = pos_full;
     }
-    launch_compact_ids(tok, pos, dedup ? Ig : nullptr, M, N, c.vocab, c.max_pos, ids_c, pos_c, hdr, stream);
+    launch_compact_ids(tok, pos, dedup ? Ig : nullptr, M, M_valid, N, c.vocab, c.max_pos, ids_c, pos_c, hdr, stream);
     launch_embed(model->embed, c.dtype, ids_c, M, d, h, stream);
-    if (fused) launch_rep_start(cu, Is, Ig, B, N, M, rep_start, stream);
+    if (fused) launch_rep_start(cu, Is, Ig, B, N, M_valid, rep_start, stream);
 
     auto gemm = [&](const void* A, const void* W, int Nout, int K, int epi, void* o) -> int {
         if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream);
@@ -349,13 +359,16 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         if (fused) {   // scatter, attention and gather in one kernel (exact): compact rows in, compact rows out
             TimedScope t(RADIX_TIME_ATTENTION, stream);
-            rc = launch_attention_mfma_fused(qkv, cu, Is, rep_start, B, N, M, max_seqlen, c.n_q_heads, c.n_kv_heads,
-                                             hd, attn_c, dt, stream);
+            rc = launch_attention_mfma_fused(qkv, cu, Is, rep_start, B, N, M_valid, max_seqlen, c.n_q_heads,
+                                             c.n_kv_heads, hd, attn_c, dt, stream);
             if (rc != RADIX_OK) return rc;
+            if (M > M_valid)    // padding rows: any defined value will do, they only feed rows nobody reads
+                launch_index_select_rows(attn_c, M_valid, nullptr, M - M_valid, (size_t)dq * es,
+                                         (char*)attn_c + (size_t)M_valid * dq * es, hdr, stream, 0);
         }
         if (dedup && !fused) {   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
             TimedScope t(RADIX_TIME_SCATTER, stream);
-            launch_index_select_rows(qkv, M, Is, N, (size_t)row * es, qkv_full, hdr, stream);
+            launch_index_select_rows(qkv, M_valid, Is, N, (size_t)row * es, qkv_full, hdr, stream);
         }
         if (!fused) {
             TimedScope t(RADIX_TIME_ATTENTION, stream);
@@ -370,7 +383,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         if (dedup && !fused) {   // Gather(a)
             TimedScope t(RADIX_TIME_GATHER, stream);
-            launch_index_select_rows(attn_full, N, Ig, M, (size_t)dq * es, attn_c, hdr, stream);
+            launch_index_select_rows(attn_full, N, Ig, M, (size_t)dq * es, attn_c, hdr, stream, M_valid);
         }
         {
             TimedScope t(RADIX_TIME_GEMM_O, stream);
@@ -399,7 +412,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     }
     if (dedup) {
         launch_rmsnorm(h, model->gf, M, d, c.eps, ynorm, RADIX_F32, stream);
-        launch_index_select_rows(ynorm, M, Is, N, (size_t)d * 4, out, hdr, stream);   // expand for output
+        launch_index_select_rows(ynorm, M_valid, Is, N, (size_t)d * 4, out, hdr, stream);   // expand for output
     } else {
         launch_rmsnorm(h, model->gf, M, d, c.eps, out, RADIX_F32, stream);
     }
@@ -433,9 +446,11 @@ extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* to
     const bool dedup = force || ((double)n_compact < (double)threshold * (double)N);
     const bool fused = opts ? opts->fused_attention != 0 : false;
     if (opts && opts->fused_attention != 0 && opts->fused_attention != 1) return RADIX_ERR_BAD_CONFIG;
+    if (opts && opts->pad_compact_to < 0) return RADIX_ERR_BAD_CONFIG;
+    const int pad_to = opts ? opts->pad_compact_to : 0;
     if (!dedup) n_compact = N;
-    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, I_scatter, I_gather, n_compact, dedup, fused, out,
-                        ws, ws_bytes, (hipStream_t)stream);
+    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, I_scatter, I_gather, n_compact, dedup, fused,
+                        pad_to, out, ws, ws_bytes, (hipStream_t)stream);
 }
 
 extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int32_t* tok, const int32_t* pos,
@@ -443,7 +458,7 @@ extern "C" int radix_prefill_forward_nodedup(const radix_model* model, const int
                                              float* out, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_common(model, tok, cu_seqlens, B, N, max_seqlen, out, ws);
     if (rc != RADIX_OK) return rc;
-    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, false, out, ws,
+    return forward_impl(model, tok, pos, cu_seqlens, B, N, max_seqlen, nullptr, nullptr, N, false, false, 0, out, ws,
                         ws_bytes, (hipStream_t)stream);
 }
 

@@ -13,11 +13,12 @@ namespace {
 template <typename V>
 __global__ __launch_bounds__(256) void index_select_kernel(const V* __restrict__ src, int n_src_rows,
                                                            const int32_t* __restrict__ idx, int n_rows,
-                                                           int row_vecs, V* __restrict__ dst, int32_t* status) {
+                                                           int n_idx, int row_vecs, V* __restrict__ dst,
+                                                           int32_t* status) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (row >= n_rows) return;
-    int s = idx ? idx[row] : row;
+    int s = row < n_idx ? (idx ? idx[row] : row) : 0;      // padding rows of a bucketed compact space repeat row 0
     if (s < 0 || s >= n_src_rows) {
         if (lane == 0) set_status(status, RADIX_ERR_BAD_TOKEN);
         s = s < 0 ? 0 : n_src_rows - 1;
@@ -61,11 +62,14 @@ __global__ void default_positions_kernel(const int32_t* __restrict__ cu, int B, 
 }
 
 __global__ void compact_ids_kernel(const int32_t* __restrict__ tok, const int32_t* __restrict__ pos,
-                                   const int32_t* __restrict__ Ig, int M, int N, int vocab, int max_pos,
-                                   int32_t* __restrict__ ids_c, int32_t* __restrict__ pos_c, int32_t* status) {
+                                   const int32_t* __restrict__ Ig, int M, int M_valid, int N, int vocab,
+                                   int max_pos, int32_t* __restrict__ ids_c, int32_t* __restrict__ pos_c,
+                                   int32_t* status) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= M) return;
-    int i = Ig ? Ig[j] : j;
+    // rows past the N' representatives pad the compact space to its bucket: copies of the first representative
+    // (paper: Implementation Details, performance padding - "repeat I_gather[0]", and I_gather[0] is token 0)
+    int i = j < M_valid ? (Ig ? Ig[j] : j) : 0;
     if (i < 0 || i >= N) { set_status(status, RADIX_ERR_BAD_TOKEN); i = 0; }
     int t = tok[i], p = pos[i];
     if (t < 0 || t >= vocab) { set_status(status, RADIX_ERR_BAD_TOKEN); t = 0; }
@@ -205,17 +209,18 @@ void launch_bf16_to_f16(const bf16_t* src, f16_t* dst, size_t n, hipStream_t str
 }
 
 void launch_index_select_rows(const void* src, int n_src_rows, const int32_t* idx, int n_rows, size_t row_bytes,
-                              void* dst, int32_t* status, hipStream_t stream) {
+                              void* dst, int32_t* status, hipStream_t stream, int n_idx) {
     if (n_rows <= 0 || row_bytes == 0) return;
+    if (n_idx < 0) n_idx = n_rows;
     const int rows_per_block = 4;
     dim3 grid(ceil_div(n_rows, rows_per_block)), block(256);
     const bool al16 = (row_bytes % 16 == 0) && (((uintptr_t)src | (uintptr_t)dst) % 16 == 0);
     if (al16) {
         hipLaunchKernelGGL(index_select_kernel<uint4>, grid, block, 0, stream, (const uint4*)src, n_src_rows, idx,
-                           n_rows, (int)(row_bytes / 16), (uint4*)dst, status);
+                           n_rows, n_idx, (int)(row_bytes / 16), (uint4*)dst, status);
     } else {
         hipLaunchKernelGGL(index_select_kernel<uint32_t>, grid, block, 0, stream, (const uint32_t*)src, n_src_rows,
-                           idx, n_rows, (int)(row_bytes / 4), (uint32_t*)dst, status);
+                           idx, n_rows, n_idx, (int)(row_bytes / 4), (uint32_t*)dst, status);
     }
 }
 
@@ -285,11 +290,11 @@ void launch_default_positions(const int32_t* cu, int B, int N, int32_t* pos_full
     hipLaunchKernelGGL(default_positions_kernel, dim3(ceil_div(N, 256)), dim3(256), 0, stream, cu, B, N, pos_full);
 }
 
-void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* Ig, int M, int N, int vocab,
-                        int max_pos, int32_t* ids_c, int32_t* pos_c, int32_t* status, hipStream_t stream) {
+void launch_compact_ids(const int32_t* tok, const int32_t* pos, const int32_t* Ig, int M, int M_valid, int N,
+                        int vocab, int max_pos, int32_t* ids_c, int32_t* pos_c, int32_t* status, hipStream_t stream) {
     if (M <= 0) return;
-    hipLaunchKernelGGL(compact_ids_kernel, dim3(ceil_div(M, 256)), dim3(256), 0, stream, tok, pos, Ig, M, N, vocab,
-                       max_pos, ids_c, pos_c, status);
+    hipLaunchKernelGGL(compact_ids_kernel, dim3(ceil_div(M, 256)), dim3(256), 0, stream, tok, pos, Ig, M, M_valid, N,
+                       vocab, max_pos, ids_c, pos_c, status);
 }
 
 void launch_embed(const void* embed, int dtype, const int32_t* ids_c, int M, int d, float* h, hipStream_t stream) {

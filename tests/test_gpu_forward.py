@@ -231,3 +231,26 @@ def test_c5_control_batch_no_sharing():
 
 def test_c2_full_size_bf16_operands():
     _sampled_parity("C2", [0, 63], tol=TOL_BF16_OPERANDS, compute="bf16")
+
+
+def test_padding_of_the_compact_space_changes_nothing():
+    # N' rounded up to a bucket with copies of the first representative (results discarded): same outputs bit for
+    # bit, in both attention modes, also when the bucket would pass N (clamped) and when nothing is shared
+    w = synth.SynthWeights(SMALL_BF16, 36)
+    for b in (synth.multilevel_batch(8, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab),
+              synth.no_sharing_batch(9, 3, 50, SMALL_BF16.vocab)):
+        model = harness.upload_model(w)
+        run = harness.Runner(model, b.N, b.B)
+        tok, cu = harness.upload_batch(b)
+        maps = run.build_index(tok, cu)
+        base = run.forward(tok, cu, b.max_seqlen, maps, force_dedup=True).cpu().numpy()
+        for pad in (64, 256, 1 << 20):
+            for fused in (False, True):
+                y = run.forward(tok, cu, b.max_seqlen, maps, force_dedup=True, fused_attention=fused,
+                                pad_compact_to=pad).cpu().numpy()
+                assert run.status() == 0
+                assert np.array_equal(y, base), (pad, fused)
+        with pytest.raises(binding.RadixError) as e:
+            run.forward(tok, cu, b.max_seqlen, maps, pad_compact_to=-1)
+        assert e.value.code == -9
+        model.close()
