@@ -121,3 +121,24 @@ def test_bench_refuses_more_than_one_gpu():
     p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert p.returncode == 2
     assert "ONE GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def _header_struct_fields(name):
+    """Field names of `typedef struct <name> { ... } <name>;` in include/radixmlp.h, in order."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "include", "radixmlp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    body = re.search(r"typedef\s+struct\s+%s\s*\{(.*?)\}\s*%s\s*;" % (name, name), text, flags=re.S).group(1)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            fields.append(re.findall(r"[A-Za-z_][A-Za-z_0-9]*", decl)[-1])
+    return fields
+
+
+@pytest.mark.parametrize("name", ["radix_model_config", "radix_layer_weights", "radix_weights", "radix_fwd_opts"])
+def test_binding_structs_follow_the_header(name):
+    # same fields in the same order: a field added to the header and not to the binding would shift every later one
+    ctype = getattr(binding, name)
+    assert [f[0] for f in ctype._fields_] == _header_struct_fields(name)
