@@ -4,11 +4,11 @@ TEST INFRASTRUCTURE ONLY (see ``oracle/__init__.py``).  Plain Python, slow on pu
 
 Two independent implementations:
 
-* ``build_index_trie``  - the sequential trie insertion of the paper's Algorithm 2
-  ("Radix Tree Creation"): sequences are inserted one after the other from the root, a
-  node is identified by its parent and the next (token id, position id) pair, a node
-  that is created gets the next compact index and records the original position that
-  created it.
+* ``build_index_trie``  - sequential trie insertion, the computation of the paper's
+  Algorithm 2 ("Radix Tree Creation") in a structure of its own (one edge dictionary):
+  sequences are inserted one after the other from the root, a node is identified by its
+  parent and the next (token id, position id) pair, a node that is created gets the next
+  compact index and records the original position that created it.
 * ``build_index_bruteforce`` - the plain definition (Section "The RadixMLP Layout",
   paragraph "Trie Construction", and the "Index semantics" paragraph of the appendix):
   two original positions are the same node iff they have the same offset in their
@@ -50,45 +50,35 @@ def node_key(position: int, token: int) -> int:
     return (int(position) << 32) ^ int(token)
 
 
-class _Node:
-    __slots__ = ("key", "children", "compact_index")
-
-    def __init__(self, key: int):
-        self.key = key
-        self.children: List[Tuple[int, int]] = []  # (key, node index)
-        self.compact_index = -1
-
-
 def build_index_trie(tok: Sequence[int], cu_seqlens: Sequence[int],
                      pos: Optional[Sequence[int]] = None) -> Tuple[np.ndarray, np.ndarray]:
-    """Algorithm 2.  Returns (I_scatter[N], I_gather[N']) as int32 arrays."""
+    """Sequential trie insertion (what Algorithm 2 computes).  Returns (I_scatter[N], I_gather[N']) as int32 arrays.
+
+    A trie node is named by its compact index, which is its creation rank; the root ("sequence start") is -1.
+    The trie itself is one dictionary of edges, (parent node, node_key of the next token) -> child node.  Walking a
+    sequence from the root, an edge that is missing creates the child: it gets the next compact index and the
+    original position that created it becomes its I_gather entry; every original position records the node it
+    reached as its I_scatter entry.
+    """
     tok = np.asarray(tok, dtype=np.int64)
     cu = np.asarray(cu_seqlens, dtype=np.int64)
     position_ids = _positions(cu, pos)
-    nodes = [_Node(-1)]            # node 0 is the root = "sequence start"
-    next_compact = 0
-    scatter: List[int] = []
-    gather: List[int] = []
+    n = int(cu[-1]) if len(cu) else 0
+    edges = {}
+    first_position: List[int] = []              # compact index -> original position that created the node
+    scatter = np.zeros(n, dtype=np.int32)
     for s in range(len(cu) - 1):
-        parent = 0
+        node = -1
         for i in range(int(cu[s]), int(cu[s + 1])):
-            key = node_key(position_ids[i], tok[i])
-            hit = -1
-            for child_key, child_idx in nodes[parent].children:   # linear child scan
-                if child_key == key:
-                    hit = child_idx
-                    break
-            if hit < 0:
-                hit = len(nodes)
-                node = _Node(key)
-                node.compact_index = next_compact
-                next_compact += 1
-                nodes.append(node)
-                nodes[parent].children.append((key, hit))
-                gather.append(i)                                   # compact -> first original
-            parent = hit
-            scatter.append(nodes[hit].compact_index)               # original -> compact
-    return np.asarray(scatter, dtype=np.int32), np.asarray(gather, dtype=np.int32)
+            edge = (node, node_key(position_ids[i], tok[i]))
+            child = edges.get(edge)
+            if child is None:
+                child = len(first_position)
+                edges[edge] = child
+                first_position.append(i)
+            scatter[i] = child
+            node = child
+    return scatter, np.asarray(first_position, dtype=np.int32)
 
 
 def build_index_bruteforce(tok: Sequence[int], cu_seqlens: Sequence[int],
