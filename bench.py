@@ -21,9 +21,22 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 
-# HBM-side bytes per gate/up GEMM launch (fetch + write) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled
-# by the 256 MiB copy dispatch of the same run (profiles/gemm_gateup_C2_hbm_traffic.md); None where not measured.
-GATEUP_TRAFFIC_BYTES = {"C2": int(82653 * 1024 * 1.984 + 47202 * 1024)}
+
+
+def measured_traffic_bytes(key):
+    """HBM-side bytes of one gate/up GEMM launch (fetched + written) from the two rocprofv3 --pmc runs of this
+    command (FETCH_SIZE, WRITE_SIZE, each scaled by what the counter reads for the 256 MiB row copy this program
+    launches as the reference dispatch): the figure is kept in the profile summary of the workload, in a line
+    "traffic_bytes_per_launch = <integer>", so that the bench line and the committed summary cannot drift apart.
+    None where no such summary exists."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"gemm_gateup_{key}_hbm_traffic.md")
+    try:
+        m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read())
+    except OSError:
+        return None
+    return int(m.group(1)) if m else None
+
 
 WORKLOAD_TEXT = {
     "C1": "C1: tiny Qwen3-style decoder fp32, 8 seqs = 32 shared + 16 own tokens",
@@ -44,15 +57,16 @@ INDEX_SELECT_SHAPES = [(16000, 1024, 12000), (16000, 1024, 70000), (100000, 2048
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_TEXT),
+                    help="default: C4, the largest of the named single-GPU configurations")
     ap.add_argument("--fused-attention", action="store_true",
                     help="time the mode with scatter/gather folded into the attention kernel (default: the "
                          "three-kernel scatter -> attention -> gather path of Algorithm 1)")
-    ap.add_argument("--split-norm-out", choices=["auto", "0", "1", "2"], default="auto",
-                    help="hi/lo RMSNorm outputs (1: both norms, 2: pre-attention norm only); auto = the setting the "
-                         "configuration's parity test runs with (2 for C4, 0 elsewhere)")
+    ap.add_argument("--hilo-layers", type=int, default=0,
+                    help="radix_model_config.hilo_layers: 0 = decided by the library from the weights (what the parity "
+                         "tests run with), k > 0 = the first k layers, -1 = none")
     ap.add_argument("--sweep-model", choices=["0.6B", "4B", "8B"], default="0.6B", help="--workload SWEEP: model shape")
     ap.add_argument("--sweep-prefix", type=int, default=2048, help="--workload SWEEP: shared prefix length")
     ap.add_argument("--sweep-suffix", type=int, default=256, help="--workload SWEEP: suffix length")
@@ -88,15 +102,9 @@ def main() -> int:
     else:
         batch = synth.make_batch(key)
         weights = synth.make_weights(key)
-    split = (2 if key == "C4" else 0) if args.split_norm_out == "auto" else int(args.split_norm_out)
-    if split:
-        import dataclasses
-        weights = synth.SynthWeights(dataclasses.replace(weights.cfg, split_norm_out=split), weights.seed)
-    if args.lm_head:
-        import dataclasses
-        weights = synth.SynthWeights(dataclasses.replace(weights.cfg, lm_head=1), weights.seed)
     cfg = weights.cfg
-    model = harness.upload_model(weights)
+    model = harness.upload_model(weights, hilo_layers=args.hilo_layers, lm_head_mode=1 if args.lm_head else 0)
+    compute_dtype, hilo = model.compute_dtype, model.hilo_layers
     run = harness.Runner(model, batch.N, batch.B)
     tok, cu = harness.upload_batch(batch)
     N, B, max_len = batch.N, batch.B, batch.max_seqlen
@@ -126,8 +134,11 @@ def main() -> int:
     # GEMM + SwiGLU) is bracketed by HIP events on the launch stream inside the timed region
     for _ in range(args.warmup):
         n_c = step()
-    dominant = "gemm_gateup"
-    binding.radix_timing_enable([dominant], every_nth=4)     # sample: an event pair idles the GPU ~6 us
+    dominant = "gemm_gateup"        # launches of the layers without (hi, lo) inputs: one size, one flop count
+    # an event pair idles the GPU for a few microseconds around the launch it brackets: sample sparsely where a
+    # launch is short, bracket every launch where that gap is below a thousandth of it
+    sparse = 2.0 * batch.N * (2 * cfg.d_int) * cfg.d < 2e12
+    binding.radix_timing_enable([dominant], every_nth=4 if sparse else 1)
     ms_per_step = timed(step, args.steps)
     t_dom, n_dom = binding.radix_timing_collect()[dominant]
     binding.radix_timing_enable([])
@@ -169,9 +180,9 @@ def main() -> int:
     flops_dom = 2.0 * n_c * (2 * di) * d                      # one gate/up GEMM launch
     avg_dom_s = t_dom / max(n_dom, 1) * 1e-3
     achieved = flops_dom / avg_dom_s / 1e12
-    peak = PEAK_TFLOPS[cfg.compute_dtype]
+    peak = PEAK_TFLOPS[compute_dtype]
     gemm_flops_layer = n_c * (2.0 * d * (dq + 2 * dkv) + 2.0 * dq * d + 6.0 * d * di)
-    gemm_ms = sum(per_kernel[k][0] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down"))
+    gemm_ms = sum(per_kernel[k][0] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_hilo_layers"))
     lens = np.diff(batch.cu_seqlens).astype(np.float64)
     attn_flops = float(np.sum(2.0 * cfg.n_q_heads * cfg.head_dim * (lens * lens + lens))) * cfg.n_layers
     es = 2 if cfg.dtype != "f32" else 4
@@ -189,13 +200,13 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": cfg.compute_dtype,
+        "dtype": compute_dtype,
         "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[key] + (f" - Qwen3-{args.sweep_model} shape, prefix {args.sweep_prefix}, "
                                                      f"suffix {args.sweep_suffix}" if key == "SWEEP" else ""), "B": B, "N": N, "N_compact": n_c,
                    "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": SWEEP_SEED if key == "SWEEP" else synth.WORKLOADS[key].seed,
-                   "weights": cfg.dtype, "operands": cfg.compute_dtype, "accumulate": "f32",
-                   "split_norm_out": int(cfg.split_norm_out),
+                   "weights": cfg.dtype, "operands": compute_dtype, "accumulate": "f32",
+                   "hilo_layers": hilo,
                    "attention_mode": "fused (indexed q/k/v, representative rows only)" if fused
                    else "scatter -> attention over N rows -> gather"},
         "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
@@ -214,9 +225,8 @@ def main() -> int:
         "gather_GBps": gather_bytes * cfg.n_layers / (per_kernel["gather"][0] * 1e-3) / 1e9 if per_kernel["gather"][0] > 0 else None,
         "roofline": {"kernel": "gate/up GEMM + SwiGLU (M=N', N=2*d_int, K=d)", "bound": "mfma", "achieved": achieved,
                      "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": GATEUP_TRAFFIC_BYTES.get(key),
-                     "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom,
-                     "executed_flops_per_launch": flops_dom * (2 if cfg.split_norm_out == 1 else 1)},
+                     "traffic": measured_traffic_bytes(key),
+                     "launches_timed": n_dom, "avg_launch_us": avg_dom_s * 1e6, "flops_per_launch": flops_dom},
     }
 
     if args.lm_head:
@@ -269,35 +279,40 @@ def index_select_bench(args, torch, np, binding):
 
 
 def cpu_baseline(batch, weights, budget_s):
-    """The oracle as it stands (fp64, no deduplication), timed on the host cores on a bounded sample
-    of whole sequences of the same batch."""
+    """The oracle as it stands (fp64, no deduplication), timed on the host cores on a bounded sample of whole
+    sequences of the same batch.  The weights are drawn layer by layer while the oracle consumes them; the time
+    spent drawing them is measured and taken off the clock."""
     import torch
     from oracle import forward as oracle_forward
     cfg = weights.cfg
     embed, gf = weights.embed, weights.gf
-    layers = [weights.layer(l) for l in range(cfg.n_layers)]      # generated before the clock starts
+    lens = [int(batch.cu_seqlens[s + 1] - batch.cu_seqlens[s]) for s in range(batch.B)]
+    # sample size from a rough rate (fp64 matmuls on ~16 cores: a few hundred GFLOP/s), at least one sequence
+    flops_tok = cfg.n_layers * (2.0 * cfg.d * (cfg.dq + 2 * cfg.dkv) + 2.0 * cfg.dq * cfg.d + 6.0 * cfg.d * cfg.d_int)
+    want_tokens = budget_s * 3e11 / flops_tok
     seqs, tokens = [], 0
-    t_used, rate = 0.0, None
-    # time one sequence first, then as many more as the budget allows
-    order = list(range(batch.B))
-    i = 0
-    total_t, total_tok = 0.0, 0
-    chunk = 1
-    while i < len(order) and total_t < budget_s:
-        take = order[i:i + chunk]
-        i += len(take)
-        t0 = time.perf_counter()
-        oracle_forward.forward_nodedup(cfg, embed, layers, gf, batch.tok, batch.cu_seqlens, sequences=take)
-        dt = time.perf_counter() - t0
-        total_t += dt
-        total_tok += int(sum(batch.cu_seqlens[s + 1] - batch.cu_seqlens[s] for s in take))
-        seqs += take
-        if total_t > 0:
-            per_seq = total_t / len(seqs)
-            chunk = max(1, min(8, int((budget_s - total_t) / max(per_seq, 1e-3) / 2)))
-    return {"value": total_tok / total_t, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"fp64 no-dedup oracle on the first {len(seqs)} whole sequences ({total_tok} tokens) of the same "
-                      f"batch, all {cfg.n_layers} layers, {total_t:.1f} s"}
+    for s in range(batch.B):
+        if seqs and tokens + lens[s] > want_tokens:
+            break
+        if lens[s] > 0:
+            seqs.append(s)
+            tokens += lens[s]
+    drawing = [0.0]
+
+    def layers():
+        for l in range(cfg.n_layers):
+            t0 = time.perf_counter()
+            lw = weights.layer(l)
+            drawing[0] += time.perf_counter() - t0
+            yield lw
+
+    t0 = time.perf_counter()
+    oracle_forward.forward_nodedup(cfg, embed, layers(), gf, batch.tok, batch.cu_seqlens, sequences=seqs)
+    total_t = time.perf_counter() - t0 - drawing[0]
+    return {"value": tokens / total_t, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"fp64 no-dedup oracle on the first {len(seqs)} whole sequences ({tokens} tokens) of the same "
+                      f"batch, all {cfg.n_layers} layers, {total_t:.1f} s (drawing the weights, {drawing[0]:.1f} s, "
+                      f"not counted)"}
 
 
 if __name__ == "__main__":

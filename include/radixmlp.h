@@ -64,12 +64,15 @@ typedef struct radix_model_config {
                               RADIX_F16 converts the weights once at create time (exact for every bf16
                               value of magnitude >= 2^-17) and carries 11-bit instead of 8-bit
                               significands through the activations; activations must stay below 65504. */
-    int32_t split_norm_out; /* 0, 1 or 2 (bf16 weights only, d a multiple of 256).  Carries RMSNorm outputs as a 16-bit
-                              (hi, lo) pair and runs the GEMM they feed over the doubled K against the weights read
-                              twice: about twice the significand on the activations that dominate the rounding
-                              error, for twice the work in that GEMM.  1: both norms of a layer (Q/K/V and gate/up
-                              GEMMs doubled); 2: the pre-attention norm only (Q/K/V GEMM doubled).  For deep, wide
-                              random-init models whose layers amplify perturbations. */
+    int32_t hilo_layers; /* Number of leading layers that carry every GEMM input (both RMSNorm outputs, the attention
+                            output, the SwiGLU output) as a 16-bit (hi, lo) pair and multiply over the doubled K against
+                            the weights read twice: about twice the significand at those rounding points for twice the
+                            GEMM work in those layers (bf16 weights only, d a multiple of 256).  Rounding errors of the
+                            first layers dominate the final error of deep models whose projections do not attenuate
+                            (their outputs are the whole residual stream at that depth).
+                            0: decided from the weights at create time: RADIX_HILO_AUTO_LAYERS layers when
+                               rms(Wq of layer 0) * sqrt(d) >= RADIX_HILO_AUTO_GAIN, else none;
+                            k > 0: the first min(k, n_layers) layers;  -1: none. */
     int32_t lm_head;     /* 0: no LM head (radix_lm_head returns RADIX_ERR_UNSUPPORTED); 1: head tied to the embedding
                             matrix; 2: separate matrix radix_weights.lm_head.  Non-zero makes radix_model_create
                             keep the head in the operand type (a converted copy of the embedding when that
@@ -77,6 +80,10 @@ typedef struct radix_model_config {
     float eps;           /* RMSNorm epsilon (inside the square root) */
     float rope_base;
 } radix_model_config;
+
+/* The automatic setting of radix_model_config.hilo_layers. */
+#define RADIX_HILO_AUTO_GAIN 0.85
+#define RADIX_HILO_AUTO_LAYERS 2
 
 /* Per-layer weights.  Matrices are [out, in] row-major as in y = W h (paper Eq. 5), stored
  * in config.dtype.  RMSNorm gains are always fp32.  All pointers are device pointers. */
@@ -134,6 +141,10 @@ typedef struct radix_fwd_opts {
 int radix_model_create(const radix_model_config* config, const radix_weights* weights, radix_model** out);
 int radix_model_destroy(radix_model* model);
 
+/* Number of leading layers the model runs with (hi, lo) GEMM inputs: what radix_model_create resolved
+ * radix_model_config.hilo_layers to (>= 0), or RADIX_ERR_NULL_POINTER. */
+int radix_model_hilo_layers(const radix_model* model);
+
 /* Bytes of workspace radix_build_index needs for batches of up to max_B sequences. */
 int radix_index_workspace_bytes(int32_t max_B, size_t* bytes_out);
 
@@ -175,7 +186,8 @@ int radix_build_index(const int32_t* tok, const int32_t* pos, const int32_t* cu_
  * scatters Q/K/V to the full ragged layout for causal varlen attention, gathers the attention
  * output back, and finally scatters the final-norm hidden state to all N rows.
  *
- *   tok, pos, cu_seqlens, B, N   as for radix_build_index (pos may be NULL)
+ *   tok, pos, cu_seqlens, B, N   as for radix_build_index (pos may be NULL); the forward calls take at most
+ *                                65535 sequences per batch (B > 65535: RADIX_ERR_UNSUPPORTED)
  *   max_seqlen                   >= longest sequence (host value; sizes the attention grid)
  *   I_scatter, I_gather, n_compact   maps from radix_build_index for this batch (n_compact on the host)
  *   opts                         NULL = {threshold 1.0, force_dedup 0}.  When the threshold says the
@@ -233,29 +245,6 @@ int radix_index_select_rows(const void* src, int32_t n_src_rows, const int32_t* 
  * recent radix_build_index / radix_prefill_forward* call that used it (each call starts by
  * clearing the status word; RADIX_OK if nothing was recorded). */
 int radix_device_status(void* ws, size_t ws_bytes, void* stream);
-
-/*
- * Optional per-kernel timing for benchmarks.  While a category's bit is set in category_mask,
- * the forward calls bracket every every_nth-th launch of that category (0 or 1: every launch) with a
- * pair of HIP events recorded on the caller's stream; an event pair costs a few microseconds of idle
- * GPU around the launch it brackets, so timing inside a timed region should sample sparsely.  radix_timing_collect waits for the device, writes for every category the
- * summed elapsed milliseconds and the number of timed launches since the last collect/enable
- * (arrays of RADIX_TIMING_CATEGORIES entries, HOST pointers) and resets the counters.
- * Process-wide state, not thread-safe; meant for one benchmarking thread.  Mask 0 disables.
- */
-enum {
-    RADIX_TIME_GEMM_QKV = 0,
-    RADIX_TIME_GEMM_O = 1,
-    RADIX_TIME_GEMM_GATEUP = 2,
-    RADIX_TIME_GEMM_DOWN = 3,
-    RADIX_TIME_ATTENTION = 4,
-    RADIX_TIME_SCATTER = 5,
-    RADIX_TIME_GATHER = 6,
-    RADIX_TIME_ROWOPS = 7,
-    RADIX_TIMING_CATEGORIES = 8
-};
-int radix_timing_enable(uint32_t category_mask, uint32_t every_nth);
-int radix_timing_collect(float* total_ms_host, int32_t* launches_host);
 
 /* Static description of a radix_status value. */
 const char* radix_status_string(int status);

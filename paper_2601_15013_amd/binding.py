@@ -19,14 +19,15 @@ RADIX_F32, RADIX_BF16, RADIX_F16 = 0, 1, 2
 _DTYPES = {"f32": RADIX_F32, "bf16": RADIX_BF16, "f16": RADIX_F16}
 
 EXPORTS = (
-    "radix_model_create", "radix_model_destroy", "radix_index_workspace_bytes", "radix_workspace_bytes",
+    "radix_model_create", "radix_model_destroy", "radix_model_hilo_layers", "radix_index_workspace_bytes", "radix_workspace_bytes",
     "radix_build_index", "radix_prefill_forward", "radix_prefill_forward_nodedup",
     "radix_lm_head_workspace_bytes", "radix_lm_head",
     "radix_index_select_rows", "radix_device_status", "radix_status_string",
     "radix_timing_enable", "radix_timing_collect",
 )
 
-TIMING_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "attention", "scatter", "gather", "rowops")
+TIMING_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "attention", "scatter", "gather", "rowops",
+                     "gemm_hilo_layers")
 
 
 class RadixError(RuntimeError):
@@ -38,7 +39,7 @@ class RadixError(RuntimeError):
 
 class radix_model_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d", "n_q_heads", "n_kv_heads", "head_dim", "d_int", "vocab",
-                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "split_norm_out", "lm_head")] + [("eps", C.c_float), ("rope_base", C.c_float)]
+                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "hilo_layers", "lm_head")] + [("eps", C.c_float), ("rope_base", C.c_float)]
 
 
 class radix_layer_weights(C.Structure):
@@ -69,6 +70,7 @@ def _lib() -> C.CDLL:
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         lib.radix_model_create.argtypes = [C.POINTER(radix_model_config), C.POINTER(radix_weights), C.POINTER(vp)]
         lib.radix_model_destroy.argtypes = [vp]
+        lib.radix_model_hilo_layers.argtypes = [vp]
         lib.radix_index_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
         lib.radix_workspace_bytes.argtypes = [vp, i32, i32, C.POINTER(sz)]
         lib.radix_build_index.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, C.POINTER(i32), vp, sz, vp]
@@ -122,6 +124,17 @@ class Model:
         self.handle = handle
         self.cfg = cfg
 
+    @property
+    def hilo_layers(self) -> int:
+        """Leading layers with (hi, lo) GEMM inputs, as resolved by radix_model_create."""
+        n = _lib().radix_model_hilo_layers(self.handle)
+        _check(min(n, 0), "radix_model_hilo_layers")
+        return n
+
+    @property
+    def compute_dtype(self) -> str:
+        return {v: k for k, v in _DTYPES.items()}[self.cfg.compute_dtype]
+
     def close(self) -> None:
         if self.handle:
             _lib().radix_model_destroy(self.handle)
@@ -134,19 +147,28 @@ class Model:
             pass
 
 
-def make_config(cfg: Any) -> radix_model_config:
-    """cfg: any object with the ModelConfig attributes (n_layers, d, n_q_heads, ...)."""
-    compute = getattr(cfg, "compute_dtype", None) or cfg.dtype
+def default_compute_dtype(weight_dtype: str) -> str:
+    """Operand type the library is used with unless a caller says otherwise: fp32 weights multiply in fp32,
+    bf16 weights as fp16 operands (see radixmlp.h, compute_dtype)."""
+    return "f32" if weight_dtype == "f32" else "f16"
+
+
+def make_config(cfg: Any, compute_dtype: Optional[str] = None, hilo_layers: int = 0,
+                lm_head: int = 0) -> radix_model_config:
+    """cfg: any object with the shape attributes (n_layers, d, n_q_heads, ..., dtype).  The library-side
+    settings are arguments of their own: compute_dtype ("f32" / "f16" / "bf16"; None = the default for the
+    weight type), hilo_layers and lm_head as in radixmlp.h."""
+    compute = compute_dtype or default_compute_dtype(cfg.dtype)
     return radix_model_config(cfg.n_layers, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_int, cfg.vocab,
                               cfg.max_pos, int(cfg.qk_norm), _DTYPES[cfg.dtype], _DTYPES[compute],
-                              int(getattr(cfg, "split_norm_out", 0)), int(getattr(cfg, "lm_head", 0)), cfg.eps,
-                              cfg.rope_base)
+                              int(hilo_layers), int(lm_head), cfg.eps, cfg.rope_base)
 
 
 def radix_model_create(cfg: Any, embed: torch.Tensor, gf: torch.Tensor,
-                       layers: Sequence[Mapping[str, torch.Tensor]], lm_head: Optional[torch.Tensor] = None) -> Model:
+                       layers: Sequence[Mapping[str, torch.Tensor]], lm_head: Optional[torch.Tensor] = None,
+                       compute_dtype: Optional[str] = None, hilo_layers: int = 0, lm_head_mode: int = 0) -> Model:
     """embed/gf/layers/lm_head: CUDA tensors ([out, in] matrices in the config dtype, fp32 gains)."""
-    c = make_config(cfg)
+    c = make_config(cfg, compute_dtype, hilo_layers, lm_head_mode)
     arr = (radix_layer_weights * len(layers))()
     for l, lw in enumerate(layers):
         for name, _ in radix_layer_weights._fields_:

@@ -3,7 +3,6 @@ from __future__ import annotations
 
 import os
 import subprocess
-import sys
 from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
@@ -53,31 +52,5 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     return LIB
 
 
-# timing probes of the GEMM main loop (stand-alone programs, not loaded by the library or the tests)
-PROBES = {"gemm_probe": [], "gemm_probe_no_loads": ["-DRADIX_GEMM_PROBE_NO_LOADS"],
-          "gemm_probe_no_frags": ["-DRADIX_GEMM_PROBE_NO_FRAGS"], "gemm_probe_no_mfma": ["-DRADIX_GEMM_PROBE_NO_MFMA"],
-          "gemm_probe_mfma_only": ["-DRADIX_GEMM_PROBE_NO_LOADS", "-DRADIX_GEMM_PROBE_NO_FRAGS"],
-          "gemm_probe_loads_only": ["-DRADIX_GEMM_PROBE_NO_MFMA", "-DRADIX_GEMM_PROBE_NO_FRAGS"]}
-
-
-def build_probes(jobs: int = 8):
-    """Compile csrc/gemm_probe.hip + gemm_mfma.hip into _build/gemm_probe*."""
-    os.makedirs(OBJ, exist_ok=True)
-    hipcc = _hipcc()
-    flags = [f for f in FLAGS if f != "-fPIC"]
-
-    def one(item):
-        name, defs = item
-        exe = os.path.join(OBJ, name)
-        _run([hipcc] + flags + defs + [os.path.join(CSRC, "gemm_probe.hip"), os.path.join(CSRC, "gemm_mfma.hip"),
-                                       "-o", exe])
-        return exe
-
-    with ThreadPoolExecutor(jobs) as ex:
-        return list(ex.map(one, PROBES.items()))
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
-    if "--probes" in sys.argv:
-        print("\n".join(build_probes()))

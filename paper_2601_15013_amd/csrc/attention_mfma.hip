@@ -62,7 +62,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
                                                                         typename Op<DT>::T* __restrict__ out,
                                                                         const int32_t* __restrict__ iscat,
                                                                         const int32_t* __restrict__ rep_start,
-                                                                        int n_compact) {
+                                                                        int n_compact, int split_out) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
@@ -276,20 +276,26 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
         }
     }
 
-    // ---- normalise and store: register e of block b is hd = 32 b + 8 (e/4) + 4 g + e%4
+    // ---- normalise and store: register e of block b is hd = 32 b + 8 (e/4) + 4 g + e%4.
+    // split_out: the row is [hi | lo] with hi = T(o) and lo = T(o - hi), for an output projection over the doubled K.
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (qi < len) {
         const float inv = 1.0f / l_tot;
         const size_t orow = FUSED ? (size_t)compact_row(qi) : (size_t)(start + qi);
-        T* op = out + orow * dq + (size_t)h * HD;
+        T* op = out + orow * (size_t)(split_out ? 2 * dq : dq) + (size_t)h * HD;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                V4 v;
+                V4 v, lo;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) v[j] = (T)(o[b][q4 * 4 + j] * inv);
+                for (int j = 0; j < 4; ++j) {
+                    const float x = o[b][q4 * 4 + j] * inv;
+                    v[j] = (T)x;
+                    lo[j] = (T)(x - (float)v[j]);
+                }
                 *reinterpret_cast<V4*>(op + b * 32 + q4 * 8 + g * 4) = v;
+                if (split_out) *reinterpret_cast<V4*>(op + dq + b * 32 + q4 * 8 + g * 4) = lo;
             }
     }
 }
@@ -298,7 +304,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
 
 static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                                 int n_kv_heads, int hd, void* out, int op_dtype, const int32_t* iscat,
-                                const int32_t* rep_start, int n_compact, hipStream_t stream) {
+                                const int32_t* rep_start, int n_compact, int split_out, hipStream_t stream) {
     const bool fused = iscat != nullptr;
     if (N <= 0 || B <= 0) return RADIX_OK;
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
@@ -318,7 +324,7 @@ static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N
     const dim3 grid((unsigned)n_blocks), block(ATT_THREADS);
 #define RADIX_ATT(DT, HPB, F)                                                                                      \
     hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB, F>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,  \
-                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, rep_start, n_compact)
+                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, rep_start, n_compact, split_out)
 #define RADIX_ATT_H(DT, F)                                                                                         \
     do {                                                                                                           \
         if (hpb == 4) RADIX_ATT(DT, 4, F); else if (hpb == 2) RADIX_ATT(DT, 2, F); else RADIX_ATT(DT, 1, F);       \
@@ -334,15 +340,15 @@ static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N
 }
 
 int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream) {
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out) {
     return launch_attention_any(qkv, cu, B, N, max_seqlen, n_q_heads, n_kv_heads, hd, out, op_dtype, nullptr, nullptr,
-                                0, stream);
+                                0, split_out, stream);
 }
 
 int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
                                 const int32_t* rep_start, int B, int N, int n_compact, int max_seqlen, int n_q_heads,
-                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream) {
+                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream, int split_out) {
     if (I_scatter == nullptr) return RADIX_ERR_BAD_SIZE;
     return launch_attention_any(qkv_c, cu, B, N, max_seqlen, n_q_heads, n_kv_heads, hd, out_c, op_dtype, I_scatter,
-                                rep_start, n_compact, stream);
+                                rep_start, n_compact, split_out, stream);
 }

@@ -33,26 +33,6 @@
 #include "common.h"
 #include "kernels.h"
 
-// Measurement probes, never defined in the library build: compile the main loop without its
-// global->LDS loads (RADIX_GEMM_PROBE_NO_LOADS), without its LDS fragment reads (.._NO_FRAGS) or
-// without its MFMAs (.._NO_MFMA) to time what remains (csrc/gemm_probe.hip).  Results are then
-// meaningless, addresses and control flow are unchanged.
-#ifdef RADIX_GEMM_PROBE_NO_FRAGS
-#define RADIX_PROBE_FRAG(x)
-#else
-#define RADIX_PROBE_FRAG(x) x
-#endif
-#ifdef RADIX_GEMM_PROBE_NO_LOADS
-#define RADIX_PROBE_LOAD(x)
-#else
-#define RADIX_PROBE_LOAD(x) x
-#endif
-#ifdef RADIX_GEMM_PROBE_NO_MFMA
-#define RADIX_PROBE_MFMA(ACC, FB, FA) asm volatile("" ::"v"(FB), "v"(FA))
-#else
-#define RADIX_PROBE_MFMA(ACC, FB, FA) ACC = Op<DT>::mfma(FB, FA, ACC)
-#endif
-
 namespace {
 
 constexpr int BK = 32;            // k-tile: 64 bytes = 4 chunks of 16 bytes per row
@@ -63,6 +43,11 @@ constexpr int GEMM_THREADS = 256;
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+// the same, and all LDS reads of this wavefront have returned (lgkmcnt = 0)
+template <int N> __device__ __forceinline__ void wait_vmcnt_and_lds() {
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
 }
 
 // Asynchronous 16-byte-per-lane copy global -> LDS: lane L of the wavefront writes LDS bytes
@@ -98,7 +83,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int A_LOADS = BM / 64, B_LOADS = BN / 64;        // 1 KB wave-loads per wavefront per k-tile
     constexpr int LOADS = A_LOADS + B_LOADS;
     constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
-    static_assert(EPI != EPI_SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
+    constexpr bool SWIGLU = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_SPLIT;
+    constexpr int PARTS = EPI == EPI_SWIGLU_SPLIT ? 2 : 1;     // (hi, lo) halves of the SwiGLU output row
+    static_assert(!SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
     static_assert(EPI != EPI_QKV_ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
     static_assert(LOADS * 2 + (BM / 64) * 2 < 64, "vmcnt range");
 
@@ -226,13 +213,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #define RADIX_MFMA_RANGE(FA, FB, LO, HI)                                                                           \
     do {                                                                                                           \
         _Pragma("unroll") for (int t = (LO); t < (HI); ++t)                                                        \
-            RADIX_PROBE_MFMA(acc[t / MB][t % MB], FB[t / MB], FA[t % MB]);                                         \
+            acc[t / MB][t % MB] = Op<DT>::mfma(FB[t / MB], FA[t % MB], acc[t / MB][t % MB]);                       \
     } while (0)
 
     // first k-step of the tile in stage CUR: its MFMAs, led by the fragment reads of its second k-step
 #define RADIX_HALF0(CUR)                                                                           \
         _Pragma("unroll") for (int u = 0; u < UNITS; ++u) {                                        \
-            RADIX_PROBE_FRAG(RADIX_FRAG1(CUR, 1, fa1, fb1, u));                                    \
+            RADIX_FRAG1(CUR, 1, fa1, fb1, u);                                                      \
             RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);                  \
             __builtin_amdgcn_sched_barrier(0);                                                     \
         }                                                                                          \
@@ -257,10 +244,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
-#ifdef RADIX_GEMM_PROBE_NO_FRAGS
-#pragma unroll
-    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 1, fa1, fb1, u);
-#endif
 
     // One k-tile = two k-steps of 16, software-pipelined over two fragment register sets and
     // scheduled by hand (the scheduling barriers pin the order): the first half of a k-step's MFMAs
@@ -282,10 +265,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
             for (int dd = 0; dd < 2 * B_LOADS; ++dd)        // load dd: row group dd / 2 of tile t+2 + dd % 2
                 if (dd * UNITS / (2 * B_LOADS) == u) {
-                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(kw, so_n, A_LOADS + dd / 2));
-                    else RADIX_PROBE_LOAD(RADIX_DMA1(kw + 1, so_n1, A_LOADS + dd / 2));
+                    if (dd % 2 == 0) RADIX_DMA1(kw, so_n, A_LOADS + dd / 2);
+                    else RADIX_DMA1(kw + 1, so_n1, A_LOADS + dd / 2);
                 }
-            RADIX_PROBE_FRAG(RADIX_FRAG1(so_e, 1, fa1, fb1, u));
+            RADIX_FRAG1(so_e, 1, fa1, fb1, u);
             RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -293,7 +276,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
-            RADIX_PROBE_FRAG(RADIX_FRAG1(so_o, 0, fa0, fb0, u));
+            RADIX_FRAG1(so_o, 0, fa0, fb0, u);
             RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -309,10 +292,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
             for (int dd = 0; dd < 2 * A_LOADS; ++dd)
                 if (dd * UNITS / (2 * A_LOADS) == u) {
-                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(ka, so_ra, dd / 2));
-                    else RADIX_PROBE_LOAD(RADIX_DMA1(ka + 1, so_e, dd / 2));       // tile t+5 goes where tile t was
+                    if (dd % 2 == 0) RADIX_DMA1(ka, so_ra, dd / 2);
+                    else RADIX_DMA1(ka + 1, so_e, dd / 2);       // tile t+5 goes where tile t was
                 }
-            RADIX_PROBE_FRAG(RADIX_FRAG1(so_n, 0, fa0, fb0, u));
+            RADIX_FRAG1(so_n, 0, fa0, fb0, u);
             RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -346,10 +329,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
-#ifdef RADIX_GEMM_PROBE_NO_FRAGS
-#pragma unroll
-    for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 1, fa1, fb1, u);
-#endif
     uint32_t so_e = 0, so_n = 2 * STAGE_B, so_w = 4 * STAGE_B;      // stages of t, t+2, t+4 (pairs are adjacent)
     for (int kt = 0; kt < KT; kt += 2) {
         const int kw = kt + 4 < KT ? kt + 4 : KT - 2;
@@ -358,10 +337,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
             for (int dd = 0; dd < 2 * B_LOADS; ++dd)
                 if (dd * UNITS / (2 * B_LOADS) == u) {
-                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(kw, so_w, A_LOADS + dd / 2));
-                    else RADIX_PROBE_LOAD(RADIX_DMA1(kw + 1, so_w + STAGE_B, A_LOADS + dd / 2));
+                    if (dd % 2 == 0) RADIX_DMA1(kw, so_w, A_LOADS + dd / 2);
+                    else RADIX_DMA1(kw + 1, so_w + STAGE_B, A_LOADS + dd / 2);
                 }
-            RADIX_PROBE_FRAG(RADIX_FRAG1(so_e, 1, fa1, fb1, u));
+            RADIX_FRAG1(so_e, 1, fa1, fb1, u);
             RADIX_MFMA_RANGE(fa0, fb0, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -369,7 +348,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < UNITS; ++u) {
-            RADIX_PROBE_FRAG(RADIX_FRAG1(so_e + STAGE_B, 0, fa0, fb0, u));
+            RADIX_FRAG1(so_e + STAGE_B, 0, fa0, fb0, u);
             RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -377,7 +356,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         __builtin_amdgcn_sched_barrier(0);
 
         RADIX_HALF0(so_e + STAGE_B)
-        wait_vmcnt<LOADS * 2>();
+        // the fragment reads just issued come from a stage that other wavefronts refill right after the
+        // barrier (activation rows of pair p+3): they must have returned before this wavefront passes it
+        wait_vmcnt_and_lds<LOADS * 2>();
         __builtin_amdgcn_s_barrier();
         const int ka = kt + 6 < KT ? kt + 6 : KT - 2;
 #pragma unroll
@@ -385,10 +366,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
             for (int dd = 0; dd < 2 * A_LOADS; ++dd)
                 if (dd * UNITS / (2 * A_LOADS) == u) {
-                    if (dd % 2 == 0) RADIX_PROBE_LOAD(RADIX_DMA1(ka, so_e, dd / 2));
-                    else RADIX_PROBE_LOAD(RADIX_DMA1(ka + 1, so_e + STAGE_B, dd / 2));
+                    if (dd % 2 == 0) RADIX_DMA1(ka, so_e, dd / 2);
+                    else RADIX_DMA1(ka + 1, so_e + STAGE_B, dd / 2);
                 }
-            RADIX_PROBE_FRAG(RADIX_FRAG1(so_n, 0, fa0, fb0, u));
+            RADIX_FRAG1(so_n, 0, fa0, fb0, u);
             RADIX_MFMA_RANGE(fa1, fb1, u * HALF / UNITS, (u + 1) * HALF / UNITS);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -449,13 +430,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         }
     } else {
         // 16-bit outputs.  EPI_STORE: 128 output columns per wavefront row (256 bytes);
-        // EPI_SWIGLU: gate block j / up block j+1 pairs -> 64 output columns per row (128 bytes).
-        constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? WTN / 2 : WTN;
+        // EPI_SWIGLU: gate block j / up block j+1 pairs -> 64 output columns per row (128 bytes);
+        // EPI_SWIGLU_SPLIT: the same twice, the rounded value into the left half of the output row and what
+        // the rounding dropped into the right half (the down projection then runs over the doubled K).
+        constexpr int OUT_COLS = SWIGLU ? WTN / 2 : WTN;
         constexpr int CHUNKS = OUT_COLS / 8;                    // 16-byte chunks per output row
         constexpr int ROWS_PER_INST = 64 / CHUNKS;
         const int orow = lane / CHUNKS, ochunk = lane % CHUNKS;
-        const int ldo = (EPI == EPI_SWIGLU) ? (Nout >> 1) : Nout;
-        const int ncol0 = (EPI == EPI_SWIGLU) ? ((n0 + wn * WTN) >> 1) : (n0 + wn * WTN);
+        const int ldo = SWIGLU ? (Nout >> 1) * PARTS : Nout;
+        const int ncol0 = SWIGLU ? ((n0 + wn * WTN) >> 1) : (n0 + wn * WTN);
         // EPI_QKV_ROPE: which head this wavefront's columns are, and whether it is rotated (q, k) or not (v)
         const int head = (n0 + wn * WTN) >> 7;
         const bool rope_head = EPI == EPI_QKV_ROPE && head < qe.n_q_heads + qe.n_kv_heads;
@@ -463,9 +446,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
         for (int ip = 0; ip < MB; ip += 2) {
 #pragma unroll
+          for (int part = 0; part < PARTS; ++part) {
+#pragma unroll
             for (int il = 0; il < 2; ++il) {
                 char* rowp = ebuf + (il * 32 + r) * PITCH;
-                if (EPI == EPI_SWIGLU) {
+                if (SWIGLU) {
 #pragma unroll
                     for (int j = 0; j < NB; j += 2)
 #pragma unroll
@@ -475,7 +460,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                             for (int t = 0; t < 4; ++t) {
                                 const float gt = acc[j][ip + il][q * 4 + t], up = acc[j + 1][ip + il][q * 4 + t];
                                 // silu(g) * u with the hardware reciprocal (1 ulp) instead of an IEEE division
-                                v[t] = (T)(gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up);
+                                const float y = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
+                                const T hi = (T)y;
+                                v[t] = part == 0 ? hi : (T)(y - (float)hi);
                             }
                             *reinterpret_cast<V4*>(rowp + ((j >> 1) * 32 + 8 * q + 4 * g) * 2) = v;
                         }
@@ -539,8 +526,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                 const int row = orow + ROWS_PER_INST * t;
                 const int gm = m0 + wm * WTM + ip * 32 + row;
                 const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * PITCH + ochunk * 16);
-                if (gm < M) *reinterpret_cast<uint4*>((T*)out_ + (size_t)gm * ldo + ncol0 + ochunk * 8) = v;
+                if (gm < M)
+                    *reinterpret_cast<uint4*>((T*)out_ + (size_t)gm * ldo + part * (Nout >> 1) + ncol0 + ochunk * 8) = v;
             }
+          }
         }
     }
     }
@@ -562,6 +551,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
     else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
     else if (epilogue == EPI_SWIGLU) RADIX_LAUNCH(EPI_SWIGLU);
+    else if (epilogue == EPI_SWIGLU_SPLIT) RADIX_LAUNCH(EPI_SWIGLU_SPLIT);
     else if (epilogue == EPI_STORE_F32) RADIX_LAUNCH(EPI_STORE_F32);
     else if (epilogue == EPI_QKV_ROPE) {
         if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_QKV_ROPE);

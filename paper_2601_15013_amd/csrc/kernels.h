@@ -51,7 +51,9 @@ enum GemmEpilogue {
     EPI_RESIDUAL = 1,  // resid[M, Nout] (fp32) += C
     EPI_SWIGLU = 2,    // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
     EPI_QKV_ROPE = 3,  // EPI_STORE of the fused q|k|v row with per-head RMSNorm and RoPE applied to q and k heads
-    EPI_STORE_F32 = 4  // C stored as fp32 (16-bit operand GEMMs only; the fp32 GEMM's EPI_STORE already is fp32)
+    EPI_STORE_F32 = 4, // C stored as fp32 (16-bit operand GEMMs only; the fp32 GEMM's EPI_STORE already is fp32)
+    EPI_SWIGLU_SPLIT = 5  // EPI_SWIGLU with the result y written as a 16-bit (hi, lo) pair: out[M, 2 (Nout/2)] holds
+                          // T(y) in columns [0, Nout/2) and T(y - T(y)) in columns [Nout/2, Nout)
 };
 // Extra inputs of EPI_QKV_ROPE (head_dim 128): gains and tables are device pointers.
 struct QkvEpilogue {
@@ -76,14 +78,16 @@ int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int e
 void launch_attention_f32(const float* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                           int n_kv_heads, int hd, float* out, hipStream_t stream);
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), head_dim 128.
+// split_out != 0: out is [N, 2 dq] and a row holds T(o) in columns [0, dq) and T(o - T(o)) in columns [dq, 2 dq).
 int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream);
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out = 0);
 // The same attention with scatter and gather folded in: q | k | v rows are read from the COMPACT buffer
 // qkv_c[n_compact, dq + 2 dkv] through I_scatter, only the representative positions of a sequence
 // ([rep_start[b], len_b), see launch_rep_start) are computed, and their rows go straight to out_c[n_compact, dq].
 int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
                                 const int32_t* rep_start, int B, int N, int n_compact, int max_seqlen, int n_q_heads,
-                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream);
+                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream,
+                                int split_out = 0);
 // rep_start[b] = first position of sequence b whose token is its own representative (len_b if none).
 void launch_rep_start(const int32_t* cu, const int32_t* I_scatter, const int32_t* I_gather, int B, int N,
                       int n_compact, int32_t* rep_start, hipStream_t stream);

@@ -6,6 +6,7 @@
 
 #include "common.h"
 #include "kernels.h"
+#include "radixmlp_bench.h"
 
 struct radix_layer_dev {
     const float *g1, *g2, *gq, *gk;
@@ -17,6 +18,7 @@ struct radix_layer_dev {
 
 struct radix_model {
     radix_model_config cfg;
+    int hilo_layers = 0;           // resolved count of leading layers that carry GEMM inputs as (hi, lo) pairs
     char* blob = nullptr;          // one device allocation holding everything below
     const void* embed = nullptr;
     const void* lm_head = nullptr;  // [vocab, d] in the operand type (may alias embed), or null
@@ -73,13 +75,30 @@ __global__ void interleave_gate_up_kernel(const uint4* __restrict__ wg, const ui
 
 __global__ void clear_status_kernel(int32_t* hdr) { hdr[0] = 0; }
 
+// Sum of squares of n 16-bit weights, one workgroup, fixed order (the result decides a setting, so it must
+// not depend on scheduling): thread t sums elements t, t + 1024, ...; then wavefront and workgroup reductions.
+__global__ __launch_bounds__(1024) void sum_squares_bf16_kernel(const bf16_t* __restrict__ w, size_t n,
+                                                                float* __restrict__ out) {
+    __shared__ float part[16];
+    float ss = 0.f;
+    for (size_t i = threadIdx.x; i < n; i += 1024) { const float v = (float)w[i]; ss += v * v; }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.f;
+        for (int k = 0; k < 16; ++k) t += part[k];
+        *out = t;
+    }
+}
+
 size_t esize(int dtype) { return dtype == RADIX_F32 ? 4 : 2; }
 
 struct WsLayout {
     size_t pos_full, ids_c, pos_c, rep_start, h, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
 };
 
-WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
+WsLayout ws_layout(const radix_model_config& c, int hilo_layers, size_t N, size_t B) {
     const size_t es = esize(c.compute_dtype);
     const size_t dq = (size_t)c.n_q_heads * c.head_dim, dkv = (size_t)c.n_kv_heads * c.head_dim;
     const size_t row = dq + 2 * dkv;
@@ -92,12 +111,13 @@ WsLayout ws_layout(const radix_model_config& c, size_t N, size_t B) {
     L.pos_c = take(M * 4);
     L.rep_start = take(B * 4);
     L.h = take(M * c.d * 4);
-    L.a = take(M * c.d * es * (c.split_norm_out ? 2 : 1));
+    const size_t w2 = hilo_layers > 0 ? 2 : 1;     // (hi, lo) rows are twice as wide
+    L.a = take(M * c.d * es * w2);
     L.qkv = take(M * row * es);
     L.qkv_full = take(N * row * es);
-    L.attn_full = take(N * dq * es);
-    L.attn_c = take(M * dq * es);
-    L.mlp = take(M * (size_t)c.d_int * es);
+    L.attn_full = take(N * dq * es * w2);
+    L.attn_c = take(M * dq * es * w2);
+    L.mlp = take(M * (size_t)c.d_int * es * w2);
     L.ynorm = take(M * c.d * 4);
     L.total = off;
     return L;
@@ -115,10 +135,10 @@ int check_config(const radix_model_config& c) {
     if (c.head_dim % 2 != 0 || c.head_dim > 128) return RADIX_ERR_UNSUPPORTED;
     if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
     if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
-    if (c.split_norm_out < 0 || c.split_norm_out > 2) return RADIX_ERR_BAD_CONFIG;
+    if (c.hilo_layers < -1) return RADIX_ERR_BAD_CONFIG;
     if (c.lm_head < 0 || c.lm_head > 2) return RADIX_ERR_BAD_CONFIG;
     if (c.lm_head && c.dtype == RADIX_BF16 && (c.vocab % 128 != 0)) return RADIX_ERR_UNSUPPORTED;
-    if (c.split_norm_out && (c.dtype != RADIX_BF16 || c.d % 256 != 0)) return RADIX_ERR_UNSUPPORTED;
+    if (c.hilo_layers > 0 && (c.dtype != RADIX_BF16 || c.d % 256 != 0)) return RADIX_ERR_UNSUPPORTED;
     if (c.dtype == RADIX_BF16) {
         // shapes the MFMA kernels cover: head_dim 128, every GEMM K a multiple of 32 and every
         // GEMM output width a multiple of 128
@@ -229,6 +249,26 @@ extern "C" int radix_model_create(const radix_model_config* config, const radix_
         L.gq = (const float*)(b + lo[l].gq); L.gk = (const float*)(b + lo[l].gk);
         L.wqkv = b + lo[l].wqkv; L.wo = b + lo[l].wo; L.wgu = b + lo[l].wgu; L.wd = b + lo[l].wd;
     }
+    // Leading layers with (hi, lo) GEMM inputs.  0 = decide from the weights: a projection with weights of
+    // root-mean-square s and fan-in d multiplies a perturbation of its (normalised) input by about s sqrt(d).
+    // Where that gain reaches 1, rounding errors made in the first layers - whose outputs ARE the residual stream
+    // at that depth - are carried undiminished through all later layers, and two layers of doubled significand
+    // remove most of the final error; below 1 they fade and the plain path is already an order of magnitude
+    // inside the tolerance.
+    m->hilo_layers = c.hilo_layers < 0 ? 0 : (c.hilo_layers < c.n_layers ? c.hilo_layers : c.n_layers);
+    if (ok && c.hilo_layers == 0 && c.dtype == RADIX_BF16 && c.d % 256 == 0) {
+        float* ss_dev = nullptr;
+        float ss = 0.f;
+        if (hipMalloc((void**)&ss_dev, sizeof(float)) != hipSuccess) ok = false;
+        if (ok) {
+            hipLaunchKernelGGL(sum_squares_bf16_kernel, dim3(1), dim3(1024), 0, 0,
+                               (const bf16_t*)weights->layers_host[0].wq, dq * d, ss_dev);
+            if (hipMemcpy(&ss, ss_dev, sizeof(float), hipMemcpyDeviceToHost) != hipSuccess) ok = false;
+            (void)hipFree(ss_dev);
+        }
+        const double gain = sqrt((double)ss / (double)(dq * d)) * sqrt((double)d);
+        if (ok && gain >= RADIX_HILO_AUTO_GAIN) m->hilo_layers = c.n_layers < RADIX_HILO_AUTO_LAYERS ? c.n_layers : RADIX_HILO_AUTO_LAYERS;
+    }
     if (ok && hipDeviceSynchronize() != hipSuccess) ok = false;
     if (ok && hipGetLastError() != hipSuccess) ok = false;
     if (!ok) {
@@ -247,10 +287,14 @@ extern "C" int radix_model_destroy(radix_model* model) {
     return e == hipSuccess ? RADIX_OK : RADIX_ERR_HIP;
 }
 
+extern "C" int radix_model_hilo_layers(const radix_model* model) {
+    return model ? model->hilo_layers : (int)RADIX_ERR_NULL_POINTER;
+}
+
 extern "C" int radix_workspace_bytes(const radix_model* model, int32_t max_N, int32_t max_B, size_t* bytes_out) {
     if (!model || !bytes_out) return RADIX_ERR_NULL_POINTER;
     if (max_N < 0 || max_B < 0) return RADIX_ERR_BAD_SIZE;
-    *bytes_out = ws_layout(model->cfg, (size_t)max_N, (size_t)max_B).total;
+    *bytes_out = ws_layout(model->cfg, model->hilo_layers, (size_t)max_N, (size_t)max_B).total;
     return RADIX_OK;
 }
 
@@ -275,7 +319,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     // path (same results) takes over
     if (fused && (long long)M * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * (long long)esize(c.compute_dtype) >= (1LL << 32))
         fused = false;
-    const WsLayout L = ws_layout(c, (size_t)N, (size_t)B);
+    const WsLayout L = ws_layout(c, model->hilo_layers, (size_t)N, (size_t)B);
     if (ws_bytes < L.total) return RADIX_ERR_WORKSPACE_TOO_SMALL;
     char* w = (char*)ws;
     int32_t* hdr = (int32_t*)w;
@@ -318,8 +362,10 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     launch_embed(model->embed, c.dtype, ids_c, M, d, h, stream);
     if (fused) launch_rep_start(cu, Is, Ig, B, N, M_valid, rep_start, stream);
 
-    auto gemm = [&](const void* A, const void* W, int Nout, int K, int epi, void* o) -> int {
-        if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream);
+    // C = A W^T over K columns of A; w_k = row length of W (K, or K / 2 when A rows are (hi, lo) pairs)
+    auto gemm = [&](const void* A, const void* W, int Nout, int K, int w_k, int epi, void* o,
+                    const QkvEpilogue* qe = nullptr) -> int {
+        if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream, qe, w_k);
         launch_gemm_f32((const float*)A, (const float*)W, M, Nout, K, epi, (float*)o, stream);
         return RADIX_OK;
     };
@@ -327,11 +373,17 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     int rc = RADIX_OK;
     for (int l = 0; l < c.n_layers; ++l) {
         const radix_layer_dev& Lw = model->layers[l];
-        const int ka = c.split_norm_out ? 2 * d : d;          // K of the QKV GEMM
-        const int kb = c.split_norm_out == 1 ? 2 * d : d;     // K of the gate/up GEMM
+        // leading layers carry every GEMM input (both norm outputs, the attention output, the SwiGLU output) as a
+        // 16-bit (hi, lo) pair and multiply over the doubled K against the weights read twice
+        const bool hl = l < model->hilo_layers;
+        const int w2 = hl ? 2 : 1;
+        // timing: the doubled GEMMs of these layers are a category of their own, so that the per-GEMM categories
+        // hold launches of one size only
+        const int t_qkv = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_QKV, t_o = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_O;
+        const int t_gu = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_GATEUP, t_dn = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_DOWN;
         {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
-            if (c.split_norm_out) {
+            if (hl) {
                 if ((rc = launch_rmsnorm_split(h, Lw.g1, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
             } else {
                 launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
@@ -340,16 +392,10 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         // Q/K-norm and RoPE ride in the QKV GEMM's epilogue when a wavefront block is one head
         const bool fused_rope = dt != RADIX_F32 && hd == 128 && row % 256 == 0;
         {
-            TimedScope t(RADIX_TIME_GEMM_QKV, stream);
-            if (fused_rope) {
-                const QkvEpilogue qe = {Lw.gq, Lw.gk, model->cos_tab, model->sin_tab, pos_c,
-                                        c.n_q_heads, c.n_kv_heads, c.qk_norm, c.eps};
-                rc = launch_gemm_mfma(a, Lw.wqkv, M, row, ka, EPI_QKV_ROPE, qkv, dt, 0, stream, &qe, d);
-            } else if (dt != RADIX_F32) {
-                rc = launch_gemm_mfma(a, Lw.wqkv, M, row, ka, EPI_STORE, qkv, dt, 0, stream, nullptr, d);
-            } else {
-                rc = gemm(a, Lw.wqkv, row, d, EPI_STORE, qkv);
-            }
+            TimedScope t(t_qkv, stream);
+            const QkvEpilogue qe = {Lw.gq, Lw.gk, model->cos_tab, model->sin_tab, pos_c,
+                                    c.n_q_heads, c.n_kv_heads, c.qk_norm, c.eps};
+            rc = gemm(a, Lw.wqkv, row, w2 * d, d, fused_rope ? EPI_QKV_ROPE : EPI_STORE, qkv, fused_rope ? &qe : nullptr);
             if (rc != RADIX_OK) return rc;
         }
         if (!fused_rope) {
@@ -357,14 +403,15 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
             launch_qknorm_rope(qkv, dt, M, c.n_q_heads, c.n_kv_heads, hd, c.qk_norm, Lw.gq, Lw.gk, c.eps, pos_c,
                                model->cos_tab, model->sin_tab, stream);
         }
+        const size_t attn_row_bytes = (size_t)w2 * dq * es;
         if (fused) {   // scatter, attention and gather in one kernel (exact): compact rows in, compact rows out
             TimedScope t(RADIX_TIME_ATTENTION, stream);
             rc = launch_attention_mfma_fused(qkv, cu, Is, rep_start, B, N, M_valid, max_seqlen, c.n_q_heads,
-                                             c.n_kv_heads, hd, attn_c, dt, stream);
+                                             c.n_kv_heads, hd, attn_c, dt, stream, hl);
             if (rc != RADIX_OK) return rc;
             if (M > M_valid)    // padding rows: any defined value will do, they only feed rows nobody reads
-                launch_index_select_rows(attn_c, M_valid, nullptr, M - M_valid, (size_t)dq * es,
-                                         (char*)attn_c + (size_t)M_valid * dq * es, hdr, stream, 0);
+                launch_index_select_rows(attn_c, M_valid, nullptr, M - M_valid, attn_row_bytes,
+                                         (char*)attn_c + (size_t)M_valid * attn_row_bytes, hdr, stream, 0);
         }
         if (dedup && !fused) {   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
             TimedScope t(RADIX_TIME_SCATTER, stream);
@@ -374,7 +421,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
             TimedScope t(RADIX_TIME_ATTENTION, stream);
             if (dt != RADIX_F32) {
                 rc = launch_attention_mfma(qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd, attn_full,
-                                           dt, stream);
+                                           dt, stream, hl);
                 if (rc != RADIX_OK) return rc;
             } else {
                 launch_attention_f32((const float*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,
@@ -383,31 +430,27 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         if (dedup && !fused) {   // Gather(a)
             TimedScope t(RADIX_TIME_GATHER, stream);
-            launch_index_select_rows(attn_full, N, Ig, M, (size_t)dq * es, attn_c, hdr, stream, M_valid);
+            launch_index_select_rows(attn_full, N, Ig, M, attn_row_bytes, attn_c, hdr, stream, M_valid);
         }
         {
-            TimedScope t(RADIX_TIME_GEMM_O, stream);
-            if ((rc = gemm(attn_c, Lw.wo, d, dq, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+            TimedScope t(t_o, stream);
+            if ((rc = gemm(attn_c, Lw.wo, d, w2 * dq, dq, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
         }
         {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
-            if (c.split_norm_out == 1) {
+            if (hl) {
                 if ((rc = launch_rmsnorm_split(h, Lw.g2, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
             } else {
                 launch_rmsnorm(h, Lw.g2, M, d, c.eps, a, dt, stream);
             }
         }
         {
-            TimedScope t(RADIX_TIME_GEMM_GATEUP, stream);
-            if (dt != RADIX_F32)
-                rc = launch_gemm_mfma(a, Lw.wgu, M, 2 * c.d_int, kb, EPI_SWIGLU, mlp, dt, 0, stream, nullptr, d);
-            else
-                rc = gemm(a, Lw.wgu, 2 * c.d_int, d, EPI_SWIGLU, mlp);
-            if (rc != RADIX_OK) return rc;
+            TimedScope t(t_gu, stream);
+            if ((rc = gemm(a, Lw.wgu, 2 * c.d_int, w2 * d, d, hl ? EPI_SWIGLU_SPLIT : EPI_SWIGLU, mlp)) != RADIX_OK) return rc;
         }
         {
-            TimedScope t(RADIX_TIME_GEMM_DOWN, stream);
-            if ((rc = gemm(mlp, Lw.wd, d, c.d_int, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+            TimedScope t(t_dn, stream);
+            if ((rc = gemm(mlp, Lw.wd, d, w2 * c.d_int, c.d_int, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
         }
     }
     if (dedup) {

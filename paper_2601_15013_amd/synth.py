@@ -17,6 +17,7 @@ N(0, 0.02) draws.
 from __future__ import annotations
 
 import dataclasses
+import os
 from concurrent.futures import ThreadPoolExecutor
 from typing import Dict, List, Optional, Sequence, Tuple
 
@@ -42,13 +43,6 @@ class ModelConfig:
     rope_base: float = 1e6
     qk_norm: bool = True
     max_pos: int = 4096
-    compute_dtype: str = ""   # operand type of the GPU path: "" = default ("f32", or "f16" for bf16 weights)
-    lm_head: int = 0         # GPU path: 0 no LM head, 1 tied to the embedding, 2 separate matrix (see radixmlp.h)
-    split_norm_out: int = 0  # GPU path: carry RMSNorm outputs as (hi, lo) pairs: 1 both norms, 2 pre-attention only (see radixmlp.h)
-
-    def __post_init__(self):
-        if not self.compute_dtype:
-            object.__setattr__(self, "compute_dtype", "f32" if self.dtype == "f32" else "f16")
 
     @property
     def dq(self) -> int:
@@ -67,9 +61,13 @@ QWEN3_8B = ModelConfig("qwen3-8b", 36, 4096, 32, 8, 128, 12288, 151936, "bf16")
 
 def _round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round fp32 values to the nearest bf16 (ties to even), returned as fp32."""
-    u = x.view(np.uint32)
-    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
-    return r.view(np.float32)
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).copy()
+    t = u >> np.uint32(16)
+    t &= np.uint32(1)
+    t += np.uint32(0x7FFF)
+    u += t                      # wraps like the 32-bit hardware add; finite inputs never reach the wrap
+    u &= np.uint32(0xFFFF0000)
+    return u.view(np.float32)
 
 
 def _normal_chunk(seed: int, tid: int, chunk: int, n: int) -> np.ndarray:
@@ -83,34 +81,40 @@ _POOL: Optional[ThreadPoolExecutor] = None
 def _pool() -> ThreadPoolExecutor:
     global _POOL
     if _POOL is None:
-        _POOL = ThreadPoolExecutor(8)
+        _POOL = ThreadPoolExecutor(max(1, min(16, os.cpu_count() or 8)))
     return _POOL
+
+
+def _chunk_jobs(seed: int, tid: int, out: np.ndarray, std: float, mean: float, bf16: bool):
+    """One job per independently keyed chunk of a flat fp32 array: draw, scale, shift, round - all in place."""
+    n = out.size
+    jobs = []
+    for c, lo in enumerate(range(0, n, _CHUNK)):
+        hi = min(n, lo + _CHUNK)
+
+        def run(c=c, lo=lo, hi=hi):
+            x = _normal_chunk(seed, tid, c, hi - lo)
+            x *= np.float32(std)
+            if mean != 0.0:
+                x += np.float32(mean)
+            out[lo:hi] = _round_to_bf16(x) if bf16 else x
+        jobs.append(run)
+    return jobs
+
+
+def _run_jobs(jobs) -> None:
+    if len(jobs) > 1:
+        list(_pool().map(lambda j: j(), jobs))
+    else:
+        for j in jobs:
+            j()
 
 
 def seeded_normal(seed: int, tid: int, shape: Tuple[int, ...], std: float, mean: float = 0.0,
                   bf16: bool = False) -> np.ndarray:
     """fp32 array of N(mean, std) draws, a pure function of (seed, tid, shape)."""
-    n = int(np.prod(shape))
-    out = np.empty(n, dtype=np.float32)
-    jobs = []
-    for c, lo in enumerate(range(0, n, _CHUNK)):
-        hi = min(n, lo + _CHUNK)
-        jobs.append((c, lo, hi))
-
-    def run(job):
-        c, lo, hi = job
-        out[lo:hi] = _normal_chunk(seed, tid, c, hi - lo)
-
-    if len(jobs) > 1:
-        list(_pool().map(run, jobs))
-    else:
-        for j in jobs:
-            run(j)
-    out *= np.float32(std)
-    if mean != 0.0:
-        out += np.float32(mean)
-    if bf16:
-        out = _round_to_bf16(out)
+    out = np.empty(int(np.prod(shape)), dtype=np.float32)
+    _run_jobs(_chunk_jobs(seed, tid, out, std, mean, bf16))
     return out.reshape(shape)
 
 
@@ -140,17 +144,24 @@ class SynthWeights:
             "wg": (c.d_int, c.d), "wu": (c.d_int, c.d), "wd": (c.d, c.d_int),
         }[name]
 
-    def tensor(self, name: str, layer: int = -1) -> np.ndarray:
+    @staticmethod
+    def _tid(name: str, layer: int) -> int:
         if name in ("embed", "gf"):
-            tid = 1 if name == "embed" else 2
-        else:
-            tid = 16 + layer * 16 + _LAYER_TENSORS.index(name)
-        gain = name.startswith("g")
-        return seeded_normal(self.seed, tid, self._shape(name), 0.02,
-                             mean=1.0 if gain else 0.0, bf16=self._bf16)
+            return 1 if name == "embed" else 2
+        return 16 + layer * 16 + _LAYER_TENSORS.index(name)
+
+    def tensor(self, name: str, layer: int = -1) -> np.ndarray:
+        return seeded_normal(self.seed, self._tid(name, layer), self._shape(name), 0.02,
+                             mean=1.0 if name.startswith("g") else 0.0, bf16=self._bf16)
 
     def layer(self, l: int) -> Dict[str, np.ndarray]:
-        return {n: self.tensor(n, l) for n in _LAYER_TENSORS}
+        """All tensors of layer l; the chunks of all of them are drawn side by side."""
+        flat = {n: np.empty(int(np.prod(self._shape(n))), dtype=np.float32) for n in _LAYER_TENSORS}
+        jobs = []
+        for n in _LAYER_TENSORS:
+            jobs += _chunk_jobs(self.seed, self._tid(n, l), flat[n], 0.02, 1.0 if n.startswith("g") else 0.0, self._bf16)
+        _run_jobs(jobs)
+        return {n: flat[n].reshape(self._shape(n)) for n in _LAYER_TENSORS}
 
     # sequence-of-layers view (lazy): ``weights.layers[l]["wq"]``
     @property

@@ -47,3 +47,18 @@ def rel_err(y, ref):
     """max |err| relative to the RMS of the oracle's output."""
     rms = float(np.sqrt(np.mean(np.asarray(ref, dtype=np.float64) ** 2)))
     return float(np.max(np.abs(np.asarray(y, dtype=np.float64) - ref))) / rms
+
+
+def rms_err(y, ref):
+    """RMS of the error relative to the RMS of the oracle's output."""
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.sqrt(np.mean((np.asarray(y, dtype=np.float64) - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
+
+
+def tail_factor(n_sampled: int, n_all: int) -> float:
+    """How much further out the largest of n_all error entries sits than the largest of n_sampled, for errors with a
+    Gaussian tail: the expected maximum of n draws of |N(0, s)| grows like s * sqrt(2 ln(2 n)).  A maximum measured on
+    a sample of the outputs is multiplied by this before it is compared with a tolerance that is meant for all of them."""
+    if n_sampled >= n_all:
+        return 1.0
+    return float(np.sqrt(np.log(2.0 * n_all) / np.log(2.0 * n_sampled)))

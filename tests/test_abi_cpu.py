@@ -20,7 +20,8 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "radixmlp.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "\n".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     declared = set(re.findall(r"^(?:int|const char\*)\s+(radix_\w+)\s*\(", header, flags=re.M))
     assert declared == set(binding.EXPORTS)
     raw = C.CDLL(binding.LIB_PATH)
@@ -75,7 +76,7 @@ def test_model_create_rejects_bad_config(lib):
     assert lib.radix_model_create(None, None, C.byref(out)) == -1
     w = binding.radix_weights(0x1000, 0x1000, None, None)
     good = dict(n_layers=1, d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_int=768, vocab=10, max_pos=16,
-                qk_norm=1, dtype=0, compute_dtype=0, split_norm_out=0, lm_head=0, eps=1e-6, rope_base=1e6)
+                qk_norm=1, dtype=0, compute_dtype=0, hilo_layers=0, lm_head=0, eps=1e-6, rope_base=1e6)
 
     def create(**kw):
         c = binding.radix_model_config(**dict(good, **kw))
@@ -87,9 +88,9 @@ def test_model_create_rejects_bad_config(lib):
     assert create(dtype=7) == -3
     assert create(dtype=1, compute_dtype=1) == -3    # 16-bit path needs head_dim 128
     assert create(compute_dtype=2) == -3         # fp32 weights are multiplied in fp32
-    assert create(split_norm_out=1) == -3        # hi/lo activations exist for 16-bit operands only
-    assert create(split_norm_out=2) == -3
-    assert create(split_norm_out=5) == -9
+    assert create(hilo_layers=1) == -3           # (hi, lo) activations exist for 16-bit operands only
+    assert create(hilo_layers=-2) == -9
+    assert create(hilo_layers=-1) == -1          # "none" is fine with fp32 weights (config passes, layers_host NULL)
     assert create(lm_head=3) == -9
     assert create(dtype=1, compute_dtype=2, head_dim=128, n_q_heads=2, n_kv_heads=1, d=256, d_int=512, vocab=1000, lm_head=1) == -3   # 16-bit head: vocab % 128
     assert create(dtype=1, compute_dtype=0, head_dim=128) == -3

@@ -2,10 +2,10 @@
 
 Tolerances (max |err| over all outputs, relative to the RMS of the oracle's output):
   fp32 configuration: 1e-4;
-  bf16-weight configurations: 2e-2 with the default fp16 operands (fp32 accumulate);
-  with bf16 operands the 8-bit significand of every activation that feeds an MFMA costs about
-  0.57 % RMS / 2.9e-2 max over 28 layers (measured and reproduced by a CPU emulation of the
-  rounding points), so that mode is held to 5e-2.
+  bf16-weight configurations: 2e-2, on the path a caller gets by default (fp16 operands, fp32 accumulate,
+  leading (hi, lo) layers decided by the library from the weights).
+Where the oracle can only afford a sample of whole sequences, the sampled maximum is scaled by
+gpu_util.tail_factor before it is compared with the tolerance, and the RMS error is printed beside it.
 """
 import dataclasses
 import numpy as np
@@ -18,12 +18,12 @@ from tests import gpu_util as U
 pytestmark = pytest.mark.gpu
 
 TOL_F32 = 1e-4
-TOL_BF16 = 2e-2          # bf16 weights, fp16 operands
-TOL_BF16_OPERANDS = 5e-2  # bf16 weights, bf16 operands
+TOL_BF16 = 2e-2          # bf16 weights
 
 
-def run_all(weights, batch, pos=None, **kw):
-    model = harness.upload_model(weights)
+def run_all(weights, batch, pos=None, compute=None, hilo=0, **kw):
+    """compute / hilo: radix_model_config.compute_dtype / hilo_layers (None / 0 = what a caller gets by default)."""
+    model = harness.upload_model(weights, compute_dtype=compute, hilo_layers=hilo)
     try:
         run = harness.Runner(model, batch.N, batch.B)
         tok, cu = harness.upload_batch(batch)
@@ -84,36 +84,53 @@ def test_fp32_no_qk_norm():
 SMALL_BF16 = synth.ModelConfig("bf16s", 3, 256, 4, 2, 128, 320, 2000, "bf16", max_pos=1024)
 
 
-@pytest.mark.parametrize("compute,tol", [("f16", TOL_BF16), ("bf16", TOL_BF16_OPERANDS)])
-def test_bf16_small_model_several_tiles_and_ragged_tail(compute, tol):
+def test_bf16_small_model_several_tiles_and_ragged_tail():
     # M = N' is not a multiple of any tile size; sequences span several attention tiles
-    cfg = dataclasses.replace(SMALL_BF16, compute_dtype=compute)
-    w = synth.SynthWeights(cfg, 31)
-    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, cfg.vocab)
+    w = synth.SynthWeights(SMALL_BF16, 31)
+    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab)
     y, y_nd, n_c = run_all(w, b)
     assert n_c == b.expected_n_compact and n_c % 32 != 0
     ref = U.oracle_rows(w, b)
-    print(f"small bf16-weight model, {compute} operands: err dedup={U.rel_err(y, ref):.3e}")
-    assert U.rel_err(y_nd, ref) <= tol
-    assert U.rel_err(y, ref) <= tol
+    print(f"small bf16-weight model: err dedup={U.rel_err(y, ref):.3e} rms {U.rms_err(y, ref):.3e}")
+    assert U.rel_err(y_nd, ref) <= TOL_BF16
+    assert U.rel_err(y, ref) <= TOL_BF16
     assert np.array_equal(y, y_nd)
 
 
-def test_split_norm_outputs_tighten_the_error():
-    # hi/lo RMSNorm outputs: same result to a tighter error, still row-invariant
+def test_bf16_operands_are_outside_the_parity_bar():
+    # compute_dtype RADIX_BF16 rounds every activation that feeds an MFMA to 8 significand bits; six such roundings
+    # per layer add up to more than the 2e-2 bar allows on the 28-layer configurations (tests/test_rounding_budget.py
+    # reproduces that from the oracle), so this mode carries no parity claim.  What is checked here: it runs, stays
+    # row-invariant, and its error is of the size the rounding budget predicts (a loose sanity bound).
+    w = synth.SynthWeights(SMALL_BF16, 31)
+    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab)
+    y, y_nd, _ = run_all(w, b, compute="bf16", hilo=-1)
+    ref = U.oracle_rows(w, b)
+    print(f"small bf16-weight model, bf16 operands: err dedup={U.rel_err(y, ref):.3e} rms {U.rms_err(y, ref):.3e}")
+    assert U.rel_err(y, ref) <= 5e-2
+    assert np.array_equal(y, y_nd)
+
+
+def test_hilo_layers_tighten_the_error():
+    # (hi, lo) GEMM inputs in the leading layers: same result to a tighter error, still row-invariant, in both
+    # attention modes; bf16 operands make the effect large enough to assert on a 3-layer model
     errs = {}
-    for split in (0, 2, 1):     # off, pre-attention norm only, both norms
-        cfg = dataclasses.replace(SMALL_BF16, compute_dtype="bf16", split_norm_out=split)
-        w = synth.SynthWeights(cfg, 31)
-        b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, cfg.vocab)
-        y, y_nd, _ = run_all(w, b)
-        ref = U.oracle_rows(w, b)
-        errs[split] = float(np.sqrt(np.mean((y - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))     # RMS error: stable
-        assert U.rel_err(y, ref) <= TOL_BF16_OPERANDS
-        assert np.array_equal(y, y_nd)
-    print("bf16 operands, relative RMS error with split off / pre-attention / both:", errs)
-    assert errs[1] < 0.9 * errs[0]
-    assert errs[2] < 0.95 * errs[0]
+    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab)
+    w = synth.SynthWeights(SMALL_BF16, 31)
+    ref = U.oracle_rows(w, b)
+    for hilo in (-1, 1, 3):     # none, the first layer, all three layers
+        y, y_nd, _ = run_all(w, b, compute="bf16", hilo=hilo)
+        y_f, _, _ = run_all(w, b, compute="bf16", hilo=hilo, fused_attention=True)
+        errs[hilo] = U.rms_err(y, ref)
+        assert np.array_equal(y, y_nd) and np.array_equal(y, y_f)
+    print("bf16 operands, relative RMS error with (hi, lo) inputs in no / the first / all layers:", errs)
+    assert errs[3] < 0.8 * errs[-1]
+    assert errs[1] < errs[-1]
+    # fp16 operands (the default type): all layers split must not be worse than none
+    e0 = U.rms_err(run_all(w, b, hilo=-1)[0], ref)
+    e3 = U.rms_err(run_all(w, b, hilo=3)[0], ref)
+    print("fp16 operands, relative RMS error with (hi, lo) inputs in no / all layers:", e0, e3)
+    assert e3 < e0
 
 
 def test_bf16_wide_model_uses_large_gemm_tiles():
@@ -182,55 +199,49 @@ def test_empty_batch_and_bad_inputs():
     model.close()
 
 
-def _sampled_parity(key, sequences, tol=TOL_BF16, compute=None, split=0):
-    """Full-size batch on the GPU in the benchmark's launch configuration; the oracle computes
-    whole sampled sequences (the no-dedup pass is independent per sequence)."""
+def _sampled_parity(key, sequences, tol=TOL_BF16):
+    """Full-size batch on the GPU in the benchmark's launch configuration and with the settings a caller gets by
+    default; the oracle computes whole sampled sequences (the no-dedup pass is independent per sequence).  The
+    sampled maximum is scaled to the full output (gpu_util.tail_factor) before it meets the tolerance."""
     b = synth.make_batch(key)
     w = synth.make_weights(key)
-    if compute is not None:
-        w = synth.SynthWeights(dataclasses.replace(w.cfg, compute_dtype=compute), w.seed)
-    if split:
-        w = synth.SynthWeights(dataclasses.replace(w.cfg, split_norm_out=split), w.seed)
     y, y_nd, n_c = run_all(w, b, force_dedup=True)
     assert n_c == b.expected_n_compact
     rows = U.rows_of(b, sequences)
     ref = U.oracle_rows(w, b, sequences=sequences)
     e_d, e_n = U.rel_err(y[rows], ref), U.rel_err(y_nd[rows], ref)
-    print(f"{key}: N={b.N} N'={n_c} sampled rows={len(rows)} err dedup={e_d:.3e} nodedup={e_n:.3e}")
-    assert e_d <= tol and e_n <= tol
+    f = U.tail_factor(ref.size, b.N * w.cfg.d)
+    print(f"{key}: N={b.N} N'={n_c} sampled sequences={len(sequences)} rows={len(rows)} max err dedup={e_d:.3e} "
+          f"nodedup={e_n:.3e} rms err={U.rms_err(y[rows], ref):.3e} tail factor={f:.3f} -> {e_d * f:.3e}")
+    assert e_d * f <= tol and e_n * f <= tol
     assert np.array_equal(y, y_nd)          # every row of the full batch, not just the sample
     assert np.all(np.isfinite(y))
 
 
 def test_c2_full_size_sampled_sequences():
-    _sampled_parity("C2", [0, 17, 40, 63])
+    _sampled_parity("C2", [0, 9, 17, 26, 33, 40, 52, 63])
 
 
 def test_c3_full_size_sampled_sequences():
-    # 4B shape, three-level trie (1 -> 8 -> 128): first and last sequence and one from the middle groups
-    _sampled_parity("C3", [0, 70, 127])
+    # 4B shape, three-level trie (1 -> 8 -> 128): one sequence of every query group (16 consecutive sequences each)
+    _sampled_parity("C3", [0, 21, 38, 59, 70, 91, 108, 127])
 
 
 def test_c4_full_size_sampled_sequences():
-    # 8B shape, 256 sequences.  With N(0, 0.02) weights at d = 4096 every layer amplifies perturbations
-    # (projection gain 0.02 * sqrt(4096) = 1.28 > 1), so fp16 activation rounding that costs 3e-3 on the
-    # 0.6B shape reaches ~2.1e-2 here after 36 layers; a hi/lo pre-attention RMSNorm output (the largest single
-    # share of that variance, 29 %) brings it to ~1.7e-2 for one doubled GEMM.
-    _sampled_parity("C4", [0, 255], split=2)
+    # 8B shape, 256 sequences, eight of them spread over the batch.  With N(0, 0.02) weights at d = 4096 a projection
+    # has gain 0.02 * sqrt(4096) = 1.28: the library finds that from the weights and runs its first layers with
+    # (hi, lo) GEMM inputs (plain fp16 operands everywhere measure 2.1e-2 here)
+    _sampled_parity("C4", [0, 37, 74, 111, 148, 185, 222, 255])
 
 
 def test_c5_full_size_sampled_sequences():
     # long shared prefix: 2080-token sequences, ~43x compression
-    _sampled_parity("C5", [0, 127])
+    _sampled_parity("C5", [0, 42, 85, 127])
 
 
 def test_c5_control_batch_no_sharing():
     # same token count, nothing shared, deduplication forced on: identity maps, M = N
-    _sampled_parity("C5ctl", [3])
-
-
-def test_c2_full_size_bf16_operands():
-    _sampled_parity("C2", [0, 63], tol=TOL_BF16_OPERANDS, compute="bf16")
+    _sampled_parity("C5ctl", [3, 40, 77, 120])
 
 
 def test_padding_of_the_compact_space_changes_nothing():

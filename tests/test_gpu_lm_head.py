@@ -24,8 +24,8 @@ def _forward(model, batch):
 
 def test_fp32_tied_head_last_token_logits():
     b = synth.make_batch("C1")
-    w = synth.SynthWeights(dataclasses.replace(synth.make_weights("C1").cfg, lm_head=1), synth.WORKLOADS["C1"].seed)
-    model = harness.upload_model(w)
+    w = synth.make_weights("C1")
+    model = harness.upload_model(w, lm_head_mode=1)
     run, maps, y = _forward(model, b)
     last = (b.cu_seqlens[1:] - 1).astype(np.int32)
     ws = binding.alloc_workspace(binding.radix_lm_head_workspace_bytes(model, len(last)))
@@ -43,14 +43,14 @@ def test_fp32_tied_head_last_token_logits():
 
 @pytest.mark.parametrize("head", [1, 2])
 def test_bf16_head_tied_and_separate_compact_space_then_scatter(head):
-    cfg = dataclasses.replace(SMALL_BF16, vocab=2048, lm_head=head)
+    cfg = dataclasses.replace(SMALL_BF16, vocab=2048)
     w = synth.SynthWeights(cfg, 51)
     lm = None
     if head == 2:
         rng = np.random.Generator(np.random.Philox(key=[51, 0x4EAD]))
         lm = synth._round_to_bf16((0.02 * rng.standard_normal((cfg.vocab, cfg.d))).astype(np.float32))
     b = synth.multilevel_batch(7, 10, 40, 2, 20, 1, 90, cfg.vocab)
-    model = harness.upload_model(w, lm_head=lm)
+    model = harness.upload_model(w, lm_head=lm, lm_head_mode=head)
     run, maps, y = _forward(model, b)
     I_s, I_g, _, n_c = maps
     w_head = w.embed if head == 1 else lm
@@ -74,9 +74,9 @@ def test_bf16_head_tied_and_separate_compact_space_then_scatter(head):
 
 
 def test_lm_head_errors_and_empty_selection():
-    cfg = dataclasses.replace(SMALL_BF16, vocab=2048, lm_head=1)
+    cfg = dataclasses.replace(SMALL_BF16, vocab=2048)
     w = synth.SynthWeights(cfg, 52)
-    model = harness.upload_model(w)
+    model = harness.upload_model(w, lm_head_mode=1)
     hidden = torch.zeros((5, cfg.d), dtype=torch.float32, device="cuda")
     ws = binding.alloc_workspace(binding.radix_lm_head_workspace_bytes(model, 8))
     out = binding.radix_lm_head(model, hidden, torch.zeros(0, dtype=torch.int32, device="cuda"), ws)
@@ -92,7 +92,7 @@ def test_lm_head_errors_and_empty_selection():
     assert e.value.code == -4
     model.close()
     # a model created without a head refuses
-    model = harness.upload_model(synth.SynthWeights(dataclasses.replace(cfg, lm_head=0), 52))
+    model = harness.upload_model(synth.SynthWeights(cfg, 52))
     with pytest.raises(binding.RadixError) as e:
         binding.radix_lm_head(model, hidden, None, ws)
     assert e.value.code == -3
@@ -102,9 +102,8 @@ def test_lm_head_errors_and_empty_selection():
 def test_c2_shape_last_token_logits():
     # full vocabulary (151 936 = 1187 x 128 columns), head tied to the embedding, B = 64 selected rows
     b = synth.make_batch("C2")
-    w0 = synth.make_weights("C2")
-    w = synth.SynthWeights(dataclasses.replace(w0.cfg, lm_head=1), w0.seed)
-    model = harness.upload_model(w)
+    w = synth.make_weights("C2")
+    model = harness.upload_model(w, lm_head_mode=1)
     run, maps, y = _forward(model, b)
     last = (b.cu_seqlens[1:] - 1).astype(np.int32)
     ws = binding.alloc_workspace(binding.radix_lm_head_workspace_bytes(model, b.B))
