@@ -42,7 +42,8 @@ typedef enum radix_status {
     RADIX_ERR_BAD_CU_SEQLENS = -6,    /* device data: cu_seqlens[0] != 0, decreasing, or last != N */
     RADIX_ERR_BAD_TOKEN = -7,         /* device data: token id < 0 or >= vocab, position id or row index out of range */
     RADIX_ERR_HIP = -8,               /* a HIP runtime call failed */
-    RADIX_ERR_BAD_CONFIG = -9         /* inconsistent model configuration */
+    RADIX_ERR_BAD_CONFIG = -9,        /* inconsistent model configuration */
+    RADIX_ERR_STATIC_LIMIT = -10      /* radix_build_index_static: more sequences than its static scratch array holds */
 } radix_status;
 
 typedef enum radix_dtype { RADIX_F32 = 0, RADIX_BF16 = 1, RADIX_F16 = 2 } radix_dtype;
@@ -178,6 +179,27 @@ int radix_build_index(const int32_t* tok, const int32_t* pos, const int32_t* cu_
                       int32_t B, int32_t N, int32_t* I_scatter, int32_t* I_gather,
                       int32_t* n_compact_dev, int32_t* n_compact_host,
                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * radix_build_index_static - radix_build_index for callers that cannot allocate device memory and so
+ * have no workspace to pass: code that runs under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, same kernels and same results as radix_build_index, minus
+ * ws / ws_bytes: the builder's state lives in a static device array inside the library
+ * (about 160 KB, held by every GPU the library runs on until the process ends).  The call allocates
+ * nothing and frees nothing.
+ *   - At most RADIX_STATIC_INDEX_MAX_B sequences; more returns RADIX_ERR_STATIC_LIMIT before anything is
+ *     launched.  N is not limited (the array holds per-sequence state only).
+ *   - All calls on one GPU share that GPU's array: calls whose device work may overlap (different
+ *     streams without ordering between them) race.  The array keeps the last call's contents; the
+ *     kernels re-initialise every word they read, so nothing needs clearing between calls.
+ *   - With n_compact_host == NULL nothing synchronises (graph capture: pass NULL).  Device-data errors are
+ *     returned only when n_compact_host is given; there is no workspace for radix_device_status to
+ *     read.  On a malformed cu_seqlens the maps are left untouched and n_compact_dev is set to 0.
+ */
+#define RADIX_STATIC_INDEX_MAX_B 4096
+int radix_build_index_static(const int32_t* tok, const int32_t* pos, const int32_t* cu_seqlens,
+                             int32_t B, int32_t N, int32_t* I_scatter, int32_t* I_gather,
+                             int32_t* n_compact_dev, int32_t* n_compact_host, void* stream);
 
 /*
  * radix_prefill_forward - deduplicated prefill (paper Algorithm 1 up to the final norm):

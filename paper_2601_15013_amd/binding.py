@@ -20,7 +20,7 @@ _DTYPES = {"f32": RADIX_F32, "bf16": RADIX_BF16, "f16": RADIX_F16}
 
 EXPORTS = (
     "radix_model_create", "radix_model_destroy", "radix_model_hilo_layers", "radix_index_workspace_bytes", "radix_workspace_bytes",
-    "radix_build_index", "radix_prefill_forward", "radix_prefill_forward_nodedup",
+    "radix_build_index", "radix_build_index_static", "radix_prefill_forward", "radix_prefill_forward_nodedup",
     "radix_lm_head_workspace_bytes", "radix_lm_head",
     "radix_index_select_rows", "radix_device_status", "radix_status_string",
     "radix_timing_enable", "radix_timing_collect",
@@ -74,6 +74,7 @@ def _lib() -> C.CDLL:
         lib.radix_index_workspace_bytes.argtypes = [i32, C.POINTER(sz)]
         lib.radix_workspace_bytes.argtypes = [vp, i32, i32, C.POINTER(sz)]
         lib.radix_build_index.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, C.POINTER(i32), vp, sz, vp]
+        lib.radix_build_index_static.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, C.POINTER(i32), vp]
         lib.radix_prefill_forward.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, C.POINTER(radix_fwd_opts),
                                               vp, vp, sz, vp]
         lib.radix_prefill_forward_nodedup.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
@@ -216,6 +217,20 @@ def radix_build_index(tok: torch.Tensor, pos: Optional[torch.Tensor], cu_seqlens
                                   C.byref(host) if sync else None, _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "radix_build_index")
     return I_scatter, I_gather, n_compact_dev, (host.value if sync else None)
+
+
+def radix_build_index_static(tok: torch.Tensor, pos: Optional[torch.Tensor], cu_seqlens: torch.Tensor,
+                             I_scatter: torch.Tensor, I_gather: torch.Tensor, n_compact_dev: torch.Tensor,
+                             sync: bool = True, stream: Optional[torch.cuda.Stream] = None) -> Optional[int]:
+    """radix_build_index without a workspace (the library's static scratch array); every buffer is the
+    caller's, nothing is allocated here or in the library.  Returns N' (None if not sync)."""
+    N, B = tok.numel(), cu_seqlens.numel() - 1
+    host = C.c_int32(-1)
+    rc = _lib().radix_build_index_static(_ptr(_i32(tok, "tok")) if N else None, _ptr(pos),
+                                         _ptr(_i32(cu_seqlens, "cu_seqlens")), B, N, _ptr(I_scatter), _ptr(I_gather),
+                                         _ptr(n_compact_dev), C.byref(host) if sync else None, _stream(stream))
+    _check(rc, "radix_build_index_static")
+    return host.value if sync else None
 
 
 def radix_prefill_forward(model: Model, tok: torch.Tensor, pos: Optional[torch.Tensor], cu_seqlens: torch.Tensor,

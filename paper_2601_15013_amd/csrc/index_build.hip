@@ -23,6 +23,8 @@
 //
 // The chain phase runs in one 1024-thread workgroup (it is latency-bound bookkeeping over B
 // sequences; the data is 4N bytes); the final map write-out is a chip-wide kernel over tokens.
+#include <mutex>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -289,19 +291,11 @@ extern "C" int radix_index_workspace_bytes(int32_t max_B, size_t* bytes_out) {
     return RADIX_OK;
 }
 
-extern "C" int radix_build_index(const int32_t* tok, const int32_t* pos, const int32_t* cu_seqlens,
-                                 int32_t B, int32_t N, int32_t* I_scatter, int32_t* I_gather,
-                                 int32_t* n_compact_dev, int32_t* n_compact_host,
-                                 void* ws, size_t ws_bytes, void* stream_) {
-    hipStream_t stream = (hipStream_t)stream_;
-    if (B < 0 || N < 0) return RADIX_ERR_BAD_SIZE;
-    if (B > (1 << 28)) return RADIX_ERR_BAD_SIZE;
-    if (!cu_seqlens || !n_compact_dev || !ws) return RADIX_ERR_NULL_POINTER;
-    if (N > 0 && (!tok || !I_scatter || !I_gather)) return RADIX_ERR_NULL_POINTER;
-    if (N > 0 && B == 0) return RADIX_ERR_BAD_SIZE;
-    if (((uintptr_t)ws & 255) != 0) return RADIX_ERR_MISALIGNED;
-    if (ws_bytes < radix_index_ws_bytes(B)) return RADIX_ERR_WORKSPACE_TOO_SMALL;
+namespace {
 
+int build_index_impl(const int32_t* tok, const int32_t* pos, const int32_t* cu_seqlens, int32_t B, int32_t N,
+                     int32_t* I_scatter, int32_t* I_gather, int32_t* n_compact_dev, int32_t* n_compact_host,
+                     void* ws, hipStream_t stream) {
     int32_t* hdr = (int32_t*)ws;
     int32_t* base = (int32_t*)((char*)ws + RADIX_WS_HEADER_BYTES);
     const size_t Bn = (size_t)(B > 0 ? B : 1);
@@ -315,6 +309,8 @@ extern "C" int radix_build_index(const int32_t* tok, const int32_t* pos, const i
     int32_t* slot_owner = cbase + Bn;
     int32_t* slot_min = slot_owner + H;
 
+    // the chain kernel initialises every word of builder state it reads (status word, per-sequence arrays, both
+    // slot tables), so the buffer may hold anything when the call starts
     hipLaunchKernelGGL(index_chain_kernel, dim3(1), dim3(IDX_THREADS), 0, stream, tok, pos, cu_seqlens, B, N,
                        I_scatter, hdr, ldr, dep, bdep, mis, myslot, cbase, slot_owner, slot_min, H, n_compact_dev);
     if (N > 0) {
@@ -330,4 +326,75 @@ extern "C" int radix_build_index(const int32_t* tok, const int32_t* pos, const i
         if (h2[0] != 0) return h2[0];
     }
     return RADIX_OK;
+}
+
+int check_index_args(const int32_t* tok, const int32_t* cu_seqlens, int32_t B, int32_t N, const int32_t* I_scatter,
+                     const int32_t* I_gather, const int32_t* n_compact_dev) {
+    if (B < 0 || N < 0) return RADIX_ERR_BAD_SIZE;
+    if (B > (1 << 28)) return RADIX_ERR_BAD_SIZE;
+    if (!cu_seqlens || !n_compact_dev) return RADIX_ERR_NULL_POINTER;
+    if (N > 0 && (!tok || !I_scatter || !I_gather)) return RADIX_ERR_NULL_POINTER;
+    if (N > 0 && B == 0) return RADIX_ERR_BAD_SIZE;
+    return RADIX_OK;
+}
+
+}  // namespace
+
+extern "C" int radix_build_index(const int32_t* tok, const int32_t* pos, const int32_t* cu_seqlens,
+                                 int32_t B, int32_t N, int32_t* I_scatter, int32_t* I_gather,
+                                 int32_t* n_compact_dev, int32_t* n_compact_host,
+                                 void* ws, size_t ws_bytes, void* stream) {
+    const int rc = check_index_args(tok, cu_seqlens, B, N, I_scatter, I_gather, n_compact_dev);
+    if (rc != RADIX_OK) return rc;
+    if (!ws) return RADIX_ERR_NULL_POINTER;
+    if (((uintptr_t)ws & 255) != 0) return RADIX_ERR_MISALIGNED;
+    if (ws_bytes < radix_index_ws_bytes(B)) return RADIX_ERR_WORKSPACE_TOO_SMALL;
+    return build_index_impl(tok, pos, cu_seqlens, B, N, I_scatter, I_gather, n_compact_dev, n_compact_host, ws,
+                            (hipStream_t)stream);
+}
+
+// ---- the same builder for callers that cannot allocate: its state lives in a static device array
+// instead of a caller-provided workspace.  Every GPU the library runs on holds its own copy of the
+// array at its own address; host code only ever uses the address hipGetSymbolAddress reports for
+// the current device (the array's name is not a device address on the host side).
+namespace {
+
+constexpr size_t STATIC_INDEX_BYTES =
+    RADIX_WS_HEADER_BYTES + ((size_t)6 * RADIX_STATIC_INDEX_MAX_B + 2 * (size_t)(2 * RADIX_STATIC_INDEX_MAX_B)) * sizeof(int32_t);
+static_assert((RADIX_STATIC_INDEX_MAX_B & (RADIX_STATIC_INDEX_MAX_B - 1)) == 0 && RADIX_STATIC_INDEX_MAX_B >= 64,
+              "the slot tables hold next_pow2(2 B) entries each");
+static __device__ __align__(256) unsigned char scratch[STATIC_INDEX_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// address of `scratch` on the current device, looked up once per device
+int static_scratch(void** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return RADIX_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return RADIX_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RADIX_OK;
+}
+
+}  // namespace
+
+extern "C" int radix_build_index_static(const int32_t* tok, const int32_t* pos, const int32_t* cu_seqlens,
+                                        int32_t B, int32_t N, int32_t* I_scatter, int32_t* I_gather,
+                                        int32_t* n_compact_dev, int32_t* n_compact_host, void* stream) {
+    int rc = check_index_args(tok, cu_seqlens, B, N, I_scatter, I_gather, n_compact_dev);
+    if (rc != RADIX_OK) return rc;
+    if (B > RADIX_STATIC_INDEX_MAX_B) return RADIX_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    if ((rc = static_scratch(&ws)) != RADIX_OK) return rc;
+    return build_index_impl(tok, pos, cu_seqlens, B, N, I_scatter, I_gather, n_compact_dev, n_compact_host, ws,
+                            (hipStream_t)stream);
 }

@@ -578,6 +578,7 @@ extern "C" const char* radix_status_string(int status) {
         case RADIX_ERR_BAD_TOKEN: return "token id, position id or index out of range";
         case RADIX_ERR_HIP: return "HIP runtime error";
         case RADIX_ERR_BAD_CONFIG: return "inconsistent model configuration";
+        case RADIX_ERR_STATIC_LIMIT: return "more sequences than the static scratch array of radix_build_index_static holds";
         default: return "unknown status";
     }
 }

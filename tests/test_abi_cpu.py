@@ -31,8 +31,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     assert binding.radix_status_string(0) == "ok"
-    seen = {binding.radix_status_string(c) for c in range(-9, 1)}
-    assert len(seen) == 10 and "unknown status" not in seen
+    seen = {binding.radix_status_string(c) for c in range(-10, 1)}
+    assert len(seen) == 11 and "unknown status" not in seen
     assert binding.radix_status_string(-99) == "unknown status"
 
 
