@@ -49,6 +49,14 @@ WORKLOAD_TEXT = {
              "distinct fixed-length suffixes",
 }
 SWEEP_SEED = 2001
+WORKLOAD_TEXT["SWEEPTABLE"] = ("all rows of the paper's forward-pass sweep for one model shape (Appendix, forward-pass latency "
+                              "table: B = 32, prefix {1..2048} x suffix {256, 1024}), forward time only, both attention modes")
+WORKLOAD_TEXT["INDEXBUILD"] = ("radix_build_index at the shapes of the paper's index-construction benchmark (Appendix, index "
+                              "construction: 16 384 tokens at several prefix ratios, 2048 x 512, identical / no-overlap 32 x 512, one "
+                              "sequence) and on tries that branch at every level")
+# (prefix, suffix) rows of the paper's sweep table
+SWEEP_ROWS = [(1, 256), (16, 256), (32, 256), (128, 256), (256, 256), (512, 256), (1024, 256), (2048, 256),
+              (1, 1024), (32, 1024), (128, 1024), (256, 1024), (512, 1024), (1024, 1024), (2048, 1024)]
 WORKLOAD_TEXT["INDEXSELECT"] = "row index-select at the shapes of the paper's gather/scatter kernel benchmark (Appendix, index-select kernel)"
 # (source rows, row elements, selected rows)
 INDEX_SELECT_SHAPES = [(16000, 1024, 12000), (16000, 1024, 70000), (100000, 2048, 500000), (2000, 64 * 256, 10000)]
@@ -61,9 +69,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_TEXT),
                     help="default: C4, the largest of the named single-GPU configurations")
-    ap.add_argument("--fused-attention", action="store_true",
-                    help="time the mode with scatter/gather folded into the attention kernel (default: the "
-                         "three-kernel scatter -> attention -> gather path of Algorithm 1)")
+    ap.add_argument("--three-kernel-attention", action="store_true",
+                    help="time the scatter -> attention over all N rows -> gather sequence as Algorithm 1 writes it "
+                         "(default: the library's default, one attention kernel that indexes the compact buffer; same "
+                         "values bit for bit)")
     ap.add_argument("--hilo-layers", type=int, default=0,
                     help="radix_model_config.hilo_layers: 0 = decided by the library from the weights (what the parity "
                          "tests run with), k > 0 = the first k layers, -1 = none")
@@ -94,6 +103,10 @@ def main() -> int:
     key = args.workload
     if key == "INDEXSELECT":
         return index_select_bench(args, torch, np, binding)
+    if key == "INDEXBUILD":
+        return index_build_bench(args, torch, np, binding, synth)
+    if key == "SWEEPTABLE":
+        return sweep_table_bench(args, torch, np, binding, harness, synth)
     if key == "SWEEP":
         model_cfg = {"0.6B": synth.QWEN3_0_6B, "4B": synth.QWEN3_4B, "8B": synth.QWEN3_8B}[args.sweep_model]
         batch = synth.shared_prefix_batch(SWEEP_SEED, 32, args.sweep_prefix, args.sweep_suffix, args.sweep_suffix,
@@ -114,7 +127,8 @@ def main() -> int:
     n_dev = torch.empty(1, dtype=torch.int32, device="cuda")
     force = key == "C5ctl"
 
-    fused = args.fused_attention
+    can_fuse = compute_dtype != "f32"          # the fused kernel is the 16-bit MFMA one
+    fused = can_fuse and not args.three_kernel_attention
 
     def step(fused_attention=fused):
         maps = binding.radix_build_index(tok, None, cu, run.ws, I_s, I_g, n_dev)
@@ -152,9 +166,10 @@ def main() -> int:
     t_fwd = timed(lambda: binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out,
                                                         force_dedup=force, fused_attention=fused), k2)
     # the other attention mode, for context: whole step and forward alone
-    t_step_other = timed(lambda: step(not fused), k2)
+    other = (not fused) if can_fuse else False
+    t_step_other = timed(lambda: step(other), k2)
     t_fwd_other = timed(lambda: binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws,
-                                                              out=out, force_dedup=force, fused_attention=not fused), k2)
+                                                              out=out, force_dedup=force, fused_attention=other), k2)
     t_nodedup = timed(lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, max_len, run.ws, out=out), k2)
     binding.radix_timing_enable(binding.TIMING_CATEGORIES)
     binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out, force_dedup=force,
@@ -162,7 +177,7 @@ def main() -> int:
     per_kernel = binding.radix_timing_collect()
     binding.radix_timing_enable(["attention"])
     binding.radix_prefill_forward(model, tok, None, cu, max_len, I_s, I_g, n_c, run.ws, out=out, force_dedup=force,
-                                  fused_attention=not fused)
+                                  fused_attention=other)
     attn_other_ms = binding.radix_timing_collect()["attention"][0]
     binding.radix_timing_enable([])
 
@@ -275,6 +290,110 @@ def index_select_bench(args, torch, np, binding):
                       "data": "synthetic", "config": {"workload": WORKLOAD_TEXT["INDEXSELECT"]}, "shapes": rows,
                       "roofline": {"bound": "hbm", "achieved": big["GBps"], "peak": 8000.0, "unit": "GB/s",
                                    "frac": big["GBps"] / 8000.0, "traffic": None}}))
+    return 0
+
+
+def _time_ms(torch, fn, iters, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / iters
+
+
+def sweep_table_bench(args, torch, np, binding, harness, synth):
+    """Every (prefix, suffix) row of the paper's sweep for one model shape, one model upload: forward time without
+    deduplication, with it (the library's default attention mode) and with Algorithm 1's three-kernel attention (gated
+    by the library's cost model, and with deduplication forced).
+    Timings exclude the index build, as the paper's do."""
+    model_cfg = {"0.6B": synth.QWEN3_0_6B, "4B": synth.QWEN3_4B, "8B": synth.QWEN3_8B}[args.sweep_model]
+    weights = synth.SynthWeights(model_cfg, SWEEP_SEED)
+    model = harness.upload_model(weights, hilo_layers=args.hilo_layers)
+    n_max = max(32 * (p + s) for p, s in SWEEP_ROWS)
+    run = harness.Runner(model, n_max, 32)
+    out = torch.empty((n_max, model_cfg.d), dtype=torch.float32, device="cuda")
+    rows = []
+    for prefix, suffix in SWEEP_ROWS:
+        batch = synth.shared_prefix_batch(SWEEP_SEED, 32, prefix, suffix, suffix, model_cfg.vocab, name="sweep")
+        tok, cu = harness.upload_batch(batch)
+        I_s, I_g, _, n_c = binding.radix_build_index(tok, None, cu, run.ws)
+        assert n_c == batch.expected_n_compact
+        o = out[:batch.N]
+        fwd = lambda mode, force=False: binding.radix_prefill_forward(model, tok, None, cu, batch.max_seqlen, I_s, I_g, n_c,
+                                                                      run.ws, out=o, fused_attention=mode, force_dedup=force)
+        t_nd = _time_ms(torch, lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, batch.max_seqlen,
+                                                                              run.ws, out=o), args.steps, args.warmup)
+        t_def = _time_ms(torch, lambda: fwd(None), args.steps, args.warmup)
+        t_3k = _time_ms(torch, lambda: fwd(False), args.steps, args.warmup)           # gated by the library's cost model
+        t_3k_forced = _time_ms(torch, lambda: fwd(False, True), args.steps, args.warmup)
+        assert run.status() == 0
+        rows.append({"prefix": prefix, "suffix": suffix, "N": batch.N, "N_compact": n_c, "gamma": n_c / batch.N,
+                     "nodedup_ms": t_nd, "dedup_ms": t_def, "speedup": t_nd / t_def,
+                     "three_kernel_ms": t_3k, "three_kernel_speedup": t_nd / t_3k,
+                     "three_kernel_forced_ms": t_3k_forced, "three_kernel_forced_speedup": t_nd / t_3k_forced})
+        print(f"{args.sweep_model} {prefix}/{suffix}: N {batch.N} N' {n_c} no-dedup {t_nd:.1f} ms, dedup {t_def:.1f} ms "
+              f"({t_nd / t_def:.2f}x), three-kernel attention {t_3k:.1f} ms ({t_nd / t_3k:.2f}x; deduplication forced: "
+              f"{t_3k_forced:.1f} ms, {t_nd / t_3k_forced:.2f}x)", file=sys.stderr, flush=True)
+    head = next(r for r in rows if (r["prefix"], r["suffix"]) == (2048, 256))
+    model.close()
+    print(json.dumps({"metric": "prefill tokens/s (uncompressed), forward only", "value": head["N"] / (head["dedup_ms"] * 1e-3),
+                      "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": head["dedup_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                      "dtype": model.compute_dtype, "data": "synthetic",
+                      "config": {"workload": WORKLOAD_TEXT["SWEEPTABLE"] + f" - Qwen3-{args.sweep_model} shape; headline = "
+                                 "prefix 2048 / suffix 256", "B": 32, "seed": SWEEP_SEED},
+                      "rows": rows}))
+    return 0
+
+
+def index_build_bench(args, torch, np, binding, synth):
+    """radix_build_index alone (maps + the 8-byte read-back of N'), microseconds per call."""
+    vocab = 151936
+    rng = np.random.Generator(np.random.Philox(key=[4001, 0x1B1D]))
+
+    def branching(depth, seg):
+        # 2^depth sequences over a binary trie: at every level a sequence takes one of two distinct seg-token segments
+        segs = [[rng.integers(0, vocab, size=seg, dtype=np.int64).astype(np.int32) for _ in range(2)] for _ in range(depth)]
+        for pair in segs:
+            while pair[1][0] == pair[0][0]:
+                pair[1][0] = rng.integers(0, vocab)
+        seqs = [np.concatenate([segs[l][(i >> (depth - 1 - l)) & 1] for l in range(depth)]) for i in range(1 << depth)]
+        n_c = sum((2 << l) * seg for l in range(depth))
+        return synth._assemble(f"binary trie depth {depth}", seqs, n_c)
+
+    one = synth.shared_prefix_batch(4002, 1, 0, 512, 512, vocab)
+    same = synth._assemble("32 identical x 512", [one.tok.copy() for _ in range(32)], 512)
+    cases = [("16 384 tokens = 32 x 512, prefix ratio 0.0", synth.no_sharing_batch(4003, 32, 512, vocab)),
+             ("16 384 tokens = 32 x 512, prefix ratio 0.5", synth.shared_prefix_batch(4004, 32, 256, 256, 256, vocab)),
+             ("16 384 tokens = 32 x 512, prefix ratio 1.0 (identical sequences)", same),
+             ("one sequence of 512", one),
+             ("2048 x 512, prefix ratio 0.5", synth.shared_prefix_batch(4005, 2048, 256, 256, 256, vocab)),
+             ("2048 x 512, no sharing", synth.no_sharing_batch(4006, 2048, 512, vocab)),
+             ("2048 sequences on a binary trie of depth 11 (32-token segments: a branching at every level)", branching(11, 32)),
+             ("4096 x 64, prefix ratio 0.5", synth.shared_prefix_batch(4007, 4096, 32, 32, 32, vocab))]
+    rows = []
+    for name, b in cases:
+        tok = torch.from_numpy(b.tok.astype(np.int32)).cuda()
+        cu = torch.from_numpy(b.cu_seqlens.astype(np.int32)).cuda()
+        ws = binding.alloc_workspace(binding.radix_index_workspace_bytes(b.B))
+        I_s = torch.empty(b.N, dtype=torch.int32, device="cuda")
+        I_g = torch.empty(b.N, dtype=torch.int32, device="cuda")
+        n_dev = torch.empty(1, dtype=torch.int32, device="cuda")
+        n_c = binding.radix_build_index(tok, None, cu, ws, I_s, I_g, n_dev)[3]
+        assert n_c == b.expected_n_compact, (name, n_c, b.expected_n_compact)
+        us = _time_ms(torch, lambda: binding.radix_build_index(tok, None, cu, ws, I_s, I_g, n_dev), max(args.steps, 20),
+                      args.warmup) * 1e3
+        rows.append({"case": name, "B": b.B, "N": b.N, "N_compact": n_c, "us": us, "Mtok_per_s": b.N / us})
+        print(f"{name}: B {b.B} N {b.N} N' {n_c}: {us:.1f} us ({b.N / us:.1f} M tok/s)", file=sys.stderr, flush=True)
+    big = rows[4]
+    print(json.dumps({"metric": "index build tokens/s", "value": big["N"] / (big["us"] * 1e-6), "unit": "tokens/s",
+                      "n_gpus": 1, "steps": max(args.steps, 20), "warmup": args.warmup, "ms_per_step": big["us"] * 1e-3,
+                      "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+                      "config": {"workload": WORKLOAD_TEXT["INDEXBUILD"] + "; headline = 2048 x 512, prefix ratio 0.5"},
+                      "rows": rows}))
     return 0
 
 

@@ -111,19 +111,32 @@ typedef struct radix_weights {
 
 typedef struct radix_model radix_model;      /* opaque */
 
+#define RADIX_THRESHOLD_AUTO (-1.0f)
+enum { RADIX_ATTN_AUTO = 0, RADIX_ATTN_THREE_KERNELS = 1, RADIX_ATTN_FUSED = 2 };
+
 /* Options of the deduplicated forward (paper: Limitations, "Low-redundancy batches", and
  * the radix_mlp_threshold setting of the end-to-end experiments). */
 typedef struct radix_fwd_opts {
-    float threshold;      /* deduplicate iff n_compact < threshold * N; 1.0 = whenever anything is shared */
+    float threshold;      /* deduplicate iff n_compact < threshold * N; 1.0 = whenever anything is shared, 0.0 = never
+                           * (the paper's radix_mlp_threshold).  Negative (RADIX_THRESHOLD_AUTO): the library decides.
+                           * With the fused attention kernel deduplication costs nothing when little is shared, so
+                           * that is 1.0.  With the three-kernel attention it pays for a scatter of (N' + N) q|k|v
+                           * rows per layer with the position-wise work of the N - N' rows it saves:
+                           * deduplicate iff (N - N') * F / 1.1e15 > (N' + N) * q|k|v row bytes / 5e12, F the
+                           * projection + MLP flops of one row and layer (rates: what the GEMMs and the row copy
+                           * reach on an MI355X); about N'/N < 0.89 for the 0.6B shape, < 0.99 for the 8B shape. */
     int32_t force_dedup;  /* 1: always take the deduplicated path, whatever the threshold says */
-    int32_t fused_attention; /* 0: scatter -> attention on all N rows -> gather, three kernels, as Algorithm 1
-                              *    writes them.  1: one attention kernel that reads q, k, v of the compact
-                              *    buffer through I_scatter, computes only the representative positions (the
-                              *    rows the gather would keep) and writes compact rows; same values bit for
-                              *    bit, no [N, .] copies.  16-bit operand configurations only
-                              *    (RADIX_ERR_UNSUPPORTED otherwise); ignored when the threshold turns
-                              *    deduplication off, and when the compact q|k|v buffer reaches 4 GB (the three
-                              *    kernels run instead). */
+    int32_t attention_mode;  /* How scatter -> attention -> gather (Algorithm 1) is executed on the deduplicated path.
+                              *  RADIX_ATTN_AUTO (0): the fused kernel where it applies (16-bit operand configurations,
+                              *    compact q|k|v buffer below 4 GB), else the three kernels.
+                              *  RADIX_ATTN_THREE_KERNELS (1): scatter of q|k|v to all N rows, attention on the full
+                              *    ragged layout, gather of its output: the sequence as Algorithm 1 writes it.
+                              *  RADIX_ATTN_FUSED (2): one attention kernel that reads q, k, v of the compact buffer
+                              *    through I_scatter, computes only the representative positions (the rows the gather
+                              *    would keep) and writes compact rows; same values bit for bit, no [N, .] copies.
+                              *    RADIX_ERR_UNSUPPORTED with fp32 weights; falls back to the three kernels when the
+                              *    compact q|k|v buffer reaches 4 GB.
+                              *  Ignored when the threshold turns deduplication off. */
     int32_t pad_compact_to;  /* 0 or 1: off.  k > 1: the compact space is rounded up to a multiple of k rows (never
                               *    beyond N) with copies of the first representative, whose results are discarded
                               *    (paper: Implementation Details, performance padding): the position-wise kernels
@@ -212,7 +225,7 @@ int radix_build_index_static(const int32_t* tok, const int32_t* pos, const int32
  *                                65535 sequences per batch (B > 65535: RADIX_ERR_UNSUPPORTED)
  *   max_seqlen                   >= longest sequence (host value; sizes the attention grid)
  *   I_scatter, I_gather, n_compact   maps from radix_build_index for this batch (n_compact on the host)
- *   opts                         NULL = {threshold 1.0, force_dedup 0}.  When the threshold says the
+ *   opts                         NULL = {RADIX_THRESHOLD_AUTO, force_dedup 0, RADIX_ATTN_AUTO, no padding}.  When the threshold says the
  *                                batch is not worth deduplicating the no-dedup path runs instead.
  *   out          float[N, d]     final-RMSNorm hidden state of every original token, ragged order
  *   ws, ws_bytes                 workspace of at least radix_workspace_bytes(model, N, B)

@@ -52,7 +52,7 @@ class radix_weights(C.Structure):
 
 
 class radix_fwd_opts(C.Structure):
-    _fields_ = [("threshold", C.c_float), ("force_dedup", C.c_int32), ("fused_attention", C.c_int32),
+    _fields_ = [("threshold", C.c_float), ("force_dedup", C.c_int32), ("attention_mode", C.c_int32),
                 ("pad_compact_to", C.c_int32)]
 
 
@@ -235,13 +235,16 @@ def radix_build_index_static(tok: torch.Tensor, pos: Optional[torch.Tensor], cu_
 
 def radix_prefill_forward(model: Model, tok: torch.Tensor, pos: Optional[torch.Tensor], cu_seqlens: torch.Tensor,
                           max_seqlen: int, I_scatter: torch.Tensor, I_gather: torch.Tensor, n_compact: int,
-                          ws: torch.Tensor, out: Optional[torch.Tensor] = None, threshold: float = 1.0,
+                          ws: torch.Tensor, out: Optional[torch.Tensor] = None, threshold: Optional[float] = None,
                           force_dedup: bool = False, stream: Optional[torch.cuda.Stream] = None,
-                          fused_attention: bool = False, pad_compact_to: int = 0) -> torch.Tensor:
+                          fused_attention: Optional[bool] = None, pad_compact_to: int = 0) -> torch.Tensor:
+    """fused_attention: None = RADIX_ATTN_AUTO, False = RADIX_ATTN_THREE_KERNELS, True = RADIX_ATTN_FUSED;
+    threshold: None = RADIX_THRESHOLD_AUTO."""
     N, B = tok.numel(), cu_seqlens.numel() - 1
     if out is None:
         out = torch.empty((N, model.cfg.d), dtype=torch.float32, device=cu_seqlens.device)
-    opts = radix_fwd_opts(threshold, int(force_dedup), int(fused_attention), int(pad_compact_to))
+    mode = 0 if fused_attention is None else (2 if fused_attention else 1)
+    opts = radix_fwd_opts(-1.0 if threshold is None else threshold, int(force_dedup), mode, int(pad_compact_to))
     rc = _lib().radix_prefill_forward(model.handle, _ptr(tok), _ptr(pos), _ptr(cu_seqlens), B, N, max_seqlen,
                                       _ptr(I_scatter), _ptr(I_gather), n_compact, C.byref(opts), _ptr(out),
                                       _ptr(ws), ws.numel(), _stream(stream))

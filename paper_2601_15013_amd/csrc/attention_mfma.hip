@@ -25,10 +25,15 @@
 // buffer: the row of sequence position p is I_scatter[start + p], looked up one tile ahead of the
 // K/V load that uses it.  Attention outputs at duplicate positions are thrown away by the gather
 // (Algorithm 1, "Gather attention output"), and in a trie the representative tokens of a sequence are
-// a SUFFIX of it (once a token opens a new node, so do all later ones), so the workgroups of a
-// sequence cover only positions [rep_start, len) and write their rows straight into the compact
-// attention output.  K/V tiles, their order and every row's arithmetic are those of the full-layout
-// mode, so both modes give bit-identical rows.
+// a SUFFIX of it (once a token opens a new node, so do all later ones), so only positions
+// [first representative, len) are computed and their rows go straight into the compact attention
+// output.  The work list (launch_attn_plan) cuts those positions into blocks of 32 queries, one per
+// wavefront row slot.  Where a sequence has fewer blocks left than a workgroup has slots, the leftover
+// blocks of consecutive sequences share a workgroup: all slots first walk the K/V tiles of the prefix
+// the sequences have in common (read once, no causal boundary inside), then every slot in turn walks
+// the remaining tiles of its own sequence while the other slots only help loading.  K/V tiles always
+// start at multiples of 64 keys and a row meets them in increasing order, so every row's arithmetic
+// is that of the full-layout mode and both modes give bit-identical rows.
 #include "common.h"
 #include "kernels.h"
 
@@ -61,7 +66,8 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
                                                                         int n_pairs,
                                                                         typename Op<DT>::T* __restrict__ out,
                                                                         const int32_t* __restrict__ iscat,
-                                                                        const int32_t* __restrict__ rep_start,
+                                                                        const int32_t* __restrict__ plan,
+                                                                        AttnPlanLayout pl,
                                                                         int n_compact, int split_out) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
@@ -72,45 +78,123 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     __shared__ uint4 Vs[2][TILE_SLOTS];
 
     constexpr int BQ = 128 / HPB;                       // query rows per workgroup
-    constexpr int WPH = 4 / HPB;                        // wavefronts per query head
-    // Work item = (sequence, head group, query tile).  Workgroup ids are dealt round-robin to the 8
-    // XCDs, each with its own L2: id % 8 picks the XCD, and all query tiles of one (sequence, head
-    // group) - which walk the same K/V rows - are given to the same XCD, consecutively.
+    constexpr int WPH = 4 / HPB;                        // wavefronts per query head = 32-row slots per workgroup
     const int n_hg = n_q_heads / HPB;
-    const int pair = ((int)blockIdx.x / 8 / n_qtiles) * 8 + (int)blockIdx.x % 8;    // (sequence, head group)
-    if (pair >= n_pairs) return;
-    const int seq = pair / n_hg, hgroup = pair % n_hg;
-    const int qt = n_qtiles - 1 - ((int)blockIdx.x / 8) % n_qtiles;                  // heavy (late) tiles first
-    // clamped so that a malformed cu_seqlens can never index outside the N rows
-    int start = cu[seq], end = cu[seq + 1];
-    start = start < 0 ? 0 : (start > N ? N : start);
-    end = end < start ? start : (end > N ? N : end);
-    const int len = end - start;
-    int q0 = qt * BQ;
-    if (FUSED) {
-        int first = rep_start[seq];                     // first representative position of the sequence
-        first = first < 0 ? 0 : first;
-        q0 += first;
-    }
-    if (q0 >= len) return;
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, g = lane >> 5;
+    const int wq = wave % WPH;                          // this wavefront's slot
+
+    // ---- what this workgroup works on.  Per slot: sequence bounds and the first of its 32 query positions
+    // (slot_len = 0: empty slot).  The K/V tiles come in phases: phase 0 = the first t_shared tiles, walked by all
+    // slots through the map of slot 0's sequence; phase 1 + w = the further tiles of slot w's own sequence up to
+    // its last query, walked by slot w alone.  The full-layout mode and single-sequence items are one phase 0.
+    int hgroup;
+    int slot_start[WPH], slot_len[WPH], slot_q[WPH];
+    int t_shared, n_priv[WPH];
+    if (!FUSED) {
+        // Work item = (sequence, head group, query tile).  Workgroup ids are dealt round-robin to the 8 XCDs,
+        // each with its own L2: id % 8 picks the XCD, and all query tiles of one (sequence, head group) - which
+        // walk the same K/V rows - are given to the same XCD, consecutively.
+        const int pair = ((int)blockIdx.x / 8 / n_qtiles) * 8 + (int)blockIdx.x % 8;    // (sequence, head group)
+        if (pair >= n_pairs) return;
+        const int seq = pair / n_hg;
+        hgroup = pair % n_hg;
+        const int qt = n_qtiles - 1 - ((int)blockIdx.x / 8) % n_qtiles;                  // heavy (late) tiles first
+        // clamped so that a malformed cu_seqlens can never index outside the N rows
+        int start = cu[seq], end = cu[seq + 1];
+        start = start < 0 ? 0 : (start > N ? N : start);
+        end = end < start ? start : (end > N ? N : end);
+        if (qt * BQ >= end - start) return;
+#pragma unroll
+        for (int w = 0; w < WPH; ++w) {
+            slot_start[w] = start;
+            slot_len[w] = end - start;
+            slot_q[w] = qt * BQ + 32 * w;
+            n_priv[w] = 0;
+        }
+        const int last_q = (qt * BQ + BQ - 1) < (end - start - 1) ? (qt * BQ + BQ - 1) : (end - start - 1);
+        t_shared = last_q / BKV + 1;
+    } else {
+        // Work index = XCD-major: each XCD gets a contiguous range of (head group, item), so the items that
+        // share a KV head's prefix rows share an L2.
+        const int n_items = plan[0];
+        const long long total = (long long)n_items * n_hg;
+        const long long per_xcd = (total + 7) / 8;
+        const long long wi = (long long)((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
+        if ((int)blockIdx.x / 8 >= per_xcd || wi >= total) return;
+        hgroup = (int)(wi / n_items);
+        const int item = (int)(wi % n_items);
+        const int ts = plan[pl.t_shared + item];
+        int last_tile = -1;
+#pragma unroll
+        for (int w = 0; w < WPH; ++w) {
+            const int sq = plan[pl.seq + 4 * item + w];
+            int start = 0, end = 0;
+            if (sq >= 0) {
+                start = cu[sq]; end = cu[sq + 1];
+                start = start < 0 ? 0 : (start > N ? N : start);
+                end = end < start ? start : (end > N ? N : end);
+            }
+            int q0 = plan[pl.q + 4 * item + w];
+            q0 = q0 < 0 ? 0 : q0;
+            slot_start[w] = start;
+            slot_len[w] = q0 < end - start ? end - start : 0;      // nothing to do: empty slot
+            slot_q[w] = q0;
+            const int lq = (q0 + 31) < (end - start - 1) ? (q0 + 31) : (end - start - 1);
+            n_priv[w] = slot_len[w] > 0 ? lq / BKV + 1 : 0;          // for now: all tiles of the slot
+            last_tile = n_priv[w] > last_tile ? n_priv[w] : last_tile;
+        }
+        if (last_tile <= 0) return;
+        if (ts == 0x7FFFFFFF) {                                      // one sequence: a single phase with causal masks
+            t_shared = last_tile;
+#pragma unroll
+            for (int w = 0; w < WPH; ++w) n_priv[w] = 0;
+        } else {
+            t_shared = slot_len[0] > 0 ? ts : 0;                     // phase 0 needs slot 0's map
+#pragma unroll
+            for (int w = 0; w < WPH; ++w) n_priv[w] = n_priv[w] > t_shared ? n_priv[w] - t_shared : 0;
+        }
+    }
+    int n_tiles = t_shared;
+#pragma unroll
+    for (int w = 0; w < WPH; ++w) n_tiles += n_priv[w];
+
+    const int start = slot_start[wq], len = slot_len[wq];     // this wavefront's own sequence
+    const int q0w = slot_q[wq];
     const int group = n_q_heads / n_kv_heads;
     const int h = hgroup * HPB + wave / WPH;            // query head of this wavefront
     const int kvh = (hgroup * HPB) / group;             // one KV head per workgroup: HPB divides group
-    const int wq = wave % WPH;                          // 32-row slice of the query tile
     const int dq = n_q_heads * HD, dkv = n_kv_heads * HD;
     const size_t row = (size_t)dq + 2 * (size_t)dkv;
     const uint32_t row_bytes = (uint32_t)(row * sizeof(T));
-    const char* kbase = (const char*)(qkv + (FUSED ? (size_t)0 : (size_t)start * row) + dq + (size_t)kvh * HD);
+    // K/V base: the compact buffer (FUSED: rows come from the map) or, full layout, the rows of the one sequence
+    const char* kbase = (const char*)(qkv + (FUSED ? (size_t)0 : (size_t)slot_start[0] * row) + dq + (size_t)kvh * HD);
     const char* vbase = kbase + (size_t)dkv * sizeof(T);
-    const int32_t* smap = FUSED ? iscat + start : nullptr;      // position -> compact row
-    auto compact_row = [&](int p) {                             // clamped: a bad map can never leave the buffer
-        int c = smap[p];
+    auto compact_row = [&](int seq_start, int p) {              // clamped: a bad map can never leave the buffer
+        int c = iscat[seq_start + p];
         c = c < 0 ? 0 : (c >= n_compact ? n_compact - 1 : c);
         return c;
+    };
+    // tile t of the workgroup's list -> (sequence whose keys it holds, first key); wave-uniform
+    auto tile_of = [&](int t, int& t_start, int& t_len, int& kv0) {
+        t_start = slot_start[0]; t_len = slot_len[0]; kv0 = t * BKV;
+        int rest = t - t_shared;
+#pragma unroll
+        for (int w = 0; w < WPH; ++w) {
+            if (rest >= 0 && rest < n_priv[w]) { t_start = slot_start[w]; t_len = slot_len[w]; kv0 = (t_shared + rest) * BKV; }
+            rest -= n_priv[w];
+        }
+    };
+    // which slot computes on tile t: -1 = all of them
+    auto owner_of = [&](int t) {
+        int own = -1, rest = t - t_shared;
+#pragma unroll
+        for (int w = 0; w < WPH; ++w) {
+            if (rest >= 0 && rest < n_priv[w]) own = w;
+            rest -= n_priv[w];
+        }
+        return own;
     };
 
     // ---- K/V tile loads: wavefront w fills tile rows [16 w, 16 w + 16) of K and of V, 4 rows (1 KB) per
@@ -118,38 +202,40 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     // Rows past the end of the sequence are clamped (the causal mask hides them).
     const int lrow = lane >> 4, lpc = lane & 15;
     int krow[4];                                                // FUSED: compact rows of this lane's 4 keys of the tile to issue
-    auto lookup_tile = [&](int kv0) {
+    auto lookup_tile = [&](int t) {
+        int ts, tl, kv0;
+        tile_of(t, ts, tl, kv0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             int kr = kv0 + 16 * wave + 4 * j + lrow;
-            kr = kr < len ? kr : len - 1;
-            krow[j] = compact_row(kr);
+            kr = kr < tl ? kr : tl - 1;
+            krow[j] = compact_row(ts, kr);
         }
     };
-    auto issue_tile = [&](int kv0, int stage) {
+    auto issue_tile = [&](int t, int stage) {
+        int ts, tl, kv0;
+        tile_of(t, ts, tl, kv0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = 16 * wave + 4 * j + lrow;             // tile row = key
             int kr = kv0 + r;
-            kr = kr < len ? kr : len - 1;
+            kr = kr < tl ? kr : tl - 1;
             const uint32_t rb = (uint32_t)(FUSED ? krow[j] : kr) * row_bytes;
             att_dma16(kbase, rb + 16u * (uint32_t)(lpc ^ (r & 15)), att_lds_addr(&Ks[stage][(16 * wave + 4 * j) * 16]));
             att_dma16(vbase, rb + 16u * (uint32_t)(lpc ^ ((r & 3) << 2)), att_lds_addr(&Vs[stage][(16 * wave + 4 * j) * 16]));
         }
     };
-    const int wave_qmin = q0 + wq * 32, wave_qmax = wave_qmin + 31;
-    const int last_q = (q0 + BQ - 1) < (len - 1) ? (q0 + BQ - 1) : (len - 1);
-    const int n_tiles = last_q / BKV + 1;
+    const int wave_qmin = q0w, wave_qmax = q0w + 31;
     if (FUSED) lookup_tile(0);
     issue_tile(0, 0);
-    if (FUSED && n_tiles > 1) lookup_tile(BKV);
+    if (FUSED && n_tiles > 1) lookup_tile(1);
 
     // ---- Q fragment (B operand of S^T = K Q^T): lane (n, g) holds Q[query n][16 ks + 8 g .. +8]
-    const int qi = q0 + wq * 32 + n;                    // query offset inside the sequence
-    const int qi_c = qi < len ? qi : len - 1;
+    const int qi = q0w + n;                             // query offset inside the sequence
+    const int qi_c = qi < len ? qi : (len > 0 ? len - 1 : 0);
     V8 qf[8];
     {
-        const size_t qrow = FUSED ? (size_t)compact_row(qi_c) : (size_t)(start + qi_c);
+        const size_t qrow = FUSED ? (len > 0 ? (size_t)compact_row(start, qi_c) : (size_t)0) : (size_t)(start + qi_c);
         const uint4* qp = (const uint4*)(qkv + qrow * row + (size_t)h * HD);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
@@ -175,12 +261,18 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     const int tr_chunk0 = 2 * tr_half + (tr_a >> 1);
 
     for (int t = 0; t < n_tiles; ++t) {
-        const int kv0 = t * BKV;
         const int st = t & 1;
         att_wait_vmcnt<0>();                // this wavefront's share of tile t has landed
         __syncthreads();                    // everybody's has; everybody is done with tile t-1
-        if (t + 1 < n_tiles) issue_tile(kv0 + BKV, st ^ 1);
-        if (FUSED && t + 2 < n_tiles) lookup_tile(kv0 + 2 * BKV);   // rows of tile t+2, waited for with tile t+1
+        if (t + 1 < n_tiles) issue_tile(t + 1, st ^ 1);
+        if (FUSED && t + 2 < n_tiles) lookup_tile(t + 2);   // rows of tile t+2, waited for with tile t+1
+        int kv0 = t * BKV;
+        if (FUSED) {
+            int ts_, tl_;
+            tile_of(t, ts_, tl_, kv0);
+            const int own = owner_of(t);
+            if (len <= 0 || (own >= 0 && own != wq)) continue;      // empty slot, or another slot's own tiles
+        }
         if (kv0 > wave_qmax) continue;      // whole tile is in this wavefront's future
 
         // ---- S^T = K Q^T : two 32-key blocks x 8 k-steps.  The K fragments are read from LDS four MFMAs
@@ -281,7 +373,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (qi < len) {
         const float inv = 1.0f / l_tot;
-        const size_t orow = FUSED ? (size_t)compact_row(qi) : (size_t)(start + qi);
+        const size_t orow = FUSED ? (size_t)compact_row(start, qi) : (size_t)(start + qi);
         T* op = out + orow * (size_t)(split_out ? 2 * dq : dq) + (size_t)h * HD;
 #pragma unroll
         for (int b = 0; b < 4; ++b)
@@ -304,19 +396,27 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
 
 static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                                 int n_kv_heads, int hd, void* out, int op_dtype, const int32_t* iscat,
-                                const int32_t* rep_start, int n_compact, int split_out, hipStream_t stream) {
+                                const int32_t* plan, int n_compact, int split_out, hipStream_t stream) {
     const bool fused = iscat != nullptr;
     if (N <= 0 || B <= 0) return RADIX_OK;
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
-    if (max_seqlen <= 0) return RADIX_ERR_BAD_SIZE;
+    if (!fused && max_seqlen <= 0) return RADIX_ERR_BAD_SIZE;
     if (op_dtype != RADIX_BF16 && op_dtype != RADIX_F16) return RADIX_ERR_UNSUPPORTED;
     if ((((uintptr_t)qkv | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
-    if (fused && (rep_start == nullptr || n_compact <= 0)) return RADIX_ERR_BAD_SIZE;
+    if (fused && (plan == nullptr || n_compact <= 0)) return RADIX_ERR_BAD_SIZE;
     const int group = n_q_heads / n_kv_heads;
     const int hpb = (group % 4 == 0) ? 4 : (group % 2 == 0 ? 2 : 1);    // query heads per workgroup
-    const int n_qtiles = ceil_div(max_seqlen, 128 / hpb);
-    const int n_pairs = (n_q_heads / hpb) * B;
-    const long long n_blocks = (long long)ceil_div(n_pairs, 8) * 8 * n_qtiles;
+    const AttnPlanLayout pl = attn_plan_layout((size_t)N, (size_t)B);
+    int n_qtiles = 0, n_pairs = 0;
+    long long n_blocks;
+    if (fused) {
+        // at most max_items items per head group; workgroups past the real count (known on the device) leave at once
+        n_blocks = ((long long)pl.max_items * (n_q_heads / hpb) + 7) / 8 * 8;
+    } else {
+        n_qtiles = ceil_div(max_seqlen, 128 / hpb);
+        n_pairs = (n_q_heads / hpb) * B;
+        n_blocks = (long long)ceil_div(n_pairs, 8) * 8 * n_qtiles;
+    }
     if (n_blocks > 0x7FFFFFFFLL) return RADIX_ERR_UNSUPPORTED;
     // per-lane 32-bit byte offsets: inside one sequence's K/V rows, or (fused) inside the compact buffer
     const long long span_rows = fused ? (long long)n_compact : (long long)max_seqlen;
@@ -324,7 +424,8 @@ static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N
     const dim3 grid((unsigned)n_blocks), block(ATT_THREADS);
 #define RADIX_ATT(DT, HPB, F)                                                                                      \
     hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB, F>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,  \
-                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, rep_start, n_compact, split_out)
+                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, plan, pl, n_compact,      \
+                       split_out)
 #define RADIX_ATT_H(DT, F)                                                                                         \
     do {                                                                                                           \
         if (hpb == 4) RADIX_ATT(DT, 4, F); else if (hpb == 2) RADIX_ATT(DT, 2, F); else RADIX_ATT(DT, 1, F);       \
@@ -346,9 +447,9 @@ int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int 
 }
 
 int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
-                                const int32_t* rep_start, int B, int N, int n_compact, int max_seqlen, int n_q_heads,
+                                const int32_t* plan, int B, int N, int n_compact, int n_q_heads,
                                 int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream, int split_out) {
     if (I_scatter == nullptr) return RADIX_ERR_BAD_SIZE;
-    return launch_attention_any(qkv_c, cu, B, N, max_seqlen, n_q_heads, n_kv_heads, hd, out_c, op_dtype, I_scatter,
-                                rep_start, n_compact, split_out, stream);
+    return launch_attention_any(qkv_c, cu, B, N, 0, n_q_heads, n_kv_heads, hd, out_c, op_dtype, I_scatter,
+                                plan, n_compact, split_out, stream);
 }

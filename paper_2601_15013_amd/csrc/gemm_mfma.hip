@@ -73,7 +73,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                                                                  const typename Op<DT>::T* __restrict__ W, int M,
                                                                  int Nout, int K, void* __restrict__ out_,
                                                                  int tiles_m, int tiles_n, int w_k,
-                                                                 QkvEpilogue qe) {
+                                                                 QkvEpilogue qe, ARowMap amap, NormFusion nf) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
@@ -87,6 +87,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int PARTS = EPI == EPI_SWIGLU_SPLIT ? 2 : 1;     // (hi, lo) halves of the SwiGLU output row
     static_assert(!SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
     static_assert(EPI != EPI_QKV_ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
+    static_assert(EPI != EPI_RESIDUAL_NORM || WTN == 128, "sum-of-squares slots are 128 columns = one wavefront");
     static_assert(LOADS * 2 + (BM / 64) * 2 < 64, "vmcnt range");
 
     constexpr int EPI_PITCH = 272;                             // epilogue row pitch in bytes (256 + 16 pad)
@@ -120,13 +121,25 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     // ---- global-load assignment.  Wave-load j of this wavefront fills tile rows
     // [16 (wave + 4 j), +16): lane L -> row + L / 4, LDS chunk L % 4, global chunk (L % 4) ^ swz(row).
     // Addresses are (uniform 64-bit tile base, advanced per k-tile) + (per-lane 32-bit byte offset).
+    // With a row map (amap.rows != nullptr) row m of the product is row amap.rows[m] of A: the gather in front
+    // of the output projection rides in these offsets instead of being a copy kernel of its own.  Rows at or
+    // past amap.n_valid (padding of a bucketed compact space) take source row 0; entries outside
+    // [0, amap.n_src) are clamped and reported.
     const int lrow = lane >> 2, lpc = lane & 3;
     const int m_last = M - 1 - m0;                              // last valid row of this tile (ragged M)
     uint32_t a_off[A_LOADS], w_off[B_LOADS];
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
         const int row = 16 * (wave + 4 * j) + lrow;
-        const int src = row < m_last ? row : m_last;
+        int src = row < m_last ? row : m_last;
+        if (amap.rows != nullptr) {
+            const int m = m0 + src;
+            src = m < amap.n_valid ? amap.rows[m] : 0;
+            if (src < 0 || src >= amap.n_src) {
+                set_status(amap.status, RADIX_ERR_BAD_TOKEN);
+                src = src < 0 ? 0 : amap.n_src - 1;
+            }
+        }
         a_off[j] = (uint32_t)(((size_t)src * K + 8 * (lpc ^ swz(row))) * sizeof(T));
     }
 #pragma unroll
@@ -134,7 +147,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         const int row = 16 * (wave + 4 * j) + lrow;
         w_off[j] = (uint32_t)(((size_t)row * w_k + 8 * (lpc ^ swz(row))) * sizeof(T));
     }
-    const char* a_base = (const char*)(A + (size_t)m0 * K);
+    const char* a_base = (const char*)(A + (amap.rows != nullptr ? (size_t)0 : (size_t)m0 * K));
     const char* w_base = (const char*)(W + (size_t)n0 * w_k);
     const int WKT = w_k / BK;       // k-tiles in a weight row; tiles past it wrap (A = [hi | lo] mode)
 
@@ -407,7 +420,63 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     const int lane = lane_opaque;
     const int r = lane & 31, g = lane >> 5;
 
-    if (EPI == EPI_RESIDUAL || EPI == EPI_STORE_F32) {
+    // RMSNorm folded in (consumer side): row scale of every row this lane owns
+    float rsr[MB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i) rsr[i] = 1.0f;
+    if (EPI != EPI_RESIDUAL && EPI != EPI_RESIDUAL_NORM && EPI != EPI_STORE_F32 && nf.ss_in != nullptr) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            int gm = m0 + wm * WTM + i * 32 + r;
+            gm = gm < M ? gm : M - 1;
+            const float* sp = nf.ss_in + (size_t)gm * nf.n_slots_in;
+            float ssum = 0.f;
+            for (int k = 0; k < nf.n_slots_in; k += 2) {         // fixed order: slot 0, 1, 2, ...
+                const float2 v = *reinterpret_cast<const float2*>(sp + k);
+                ssum += v.x;
+                ssum += v.y;
+            }
+            rsr[i] = 1.0f / sqrtf(ssum * nf.inv_d + nf.eps);
+        }
+    }
+#define RADIX_ACC(J, I, E) (acc[J][I][E] * rsr[I])
+
+    if (EPI == EPI_RESIDUAL_NORM) {
+        // fp32 read-modify-write of the residual stream as below, plus, per row: the updated values times the
+        // gain of the norm that follows, in the operand type (what the next projection multiplies), and the
+        // sum of their squares over this wavefront's 128 columns (in-lane in (j, q, t) order, then the partner
+        // lane that holds the other half of the row's columns)
+        const int slot = (n0 + wn * WTN) >> 7, n_slots = Nout >> 7;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int gm = m0 + wm * WTM + i * 32 + r;
+            if (gm >= M) continue;                                 // both lanes of a row leave together
+            float* orow = (float*)out_ + (size_t)gm * Nout + n0 + wn * WTN;
+            T* arow = (T*)nf.a16 + (size_t)gm * Nout + n0 + wn * WTN;
+            const float* grow = nf.gain + n0 + wn * WTN;
+            float ss = 0.f;
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c = j * 32 + 8 * q + 4 * g;
+                    f32x4* p = reinterpret_cast<f32x4*>(orow + c);
+                    f32x4 v = *p;
+                    const f32x4 gn = *reinterpret_cast<const f32x4*>(grow + c);
+                    V4 a;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        v[t] += acc[j][i][q * 4 + t];
+                        ss += v[t] * v[t];
+                        a[t] = (T)(v[t] * gn[t]);
+                    }
+                    *p = v;
+                    *reinterpret_cast<V4*>(arow + c) = a;
+                }
+            ss += __shfl_xor(ss, 32, 64);
+            if (g == 0) nf.ss_out[(size_t)gm * n_slots + slot] = ss;
+        }
+    } else if (EPI == EPI_RESIDUAL || EPI == EPI_STORE_F32) {
         // fp32 read-modify-write of the residual stream (or a plain fp32 store) straight from the accumulator layout: per
         // instruction 32 rows x 32 contiguous bytes; all loads of a row block are issued before its
         // stores, and nothing has to be converted, so the LDS detour does not pay here.
@@ -458,7 +527,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                             V4 v;
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
-                                const float gt = acc[j][ip + il][q * 4 + t], up = acc[j + 1][ip + il][q * 4 + t];
+                                const float gt = RADIX_ACC(j, ip + il, q * 4 + t), up = RADIX_ACC(j + 1, ip + il, q * 4 + t);
                                 // silu(g) * u with the hardware reciprocal (1 ulp) instead of an IEEE division
                                 const float y = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * up;
                                 const T hi = (T)y;
@@ -479,7 +548,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
 #pragma unroll
                         for (int j = 0; j < NB; ++j)
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) ss += acc[j][i][e] * acc[j][i][e];
+                            for (int e = 0; e < 16; ++e) ss += RADIX_ACC(j, i, e) * RADIX_ACC(j, i, e);
                         ss += __shfl_xor(ss, 32, 64);
                         rs = 1.0f / sqrtf(ss * (1.0f / 128.0f) + qe.eps);
                     }
@@ -500,8 +569,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                             V4 va, vb;
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
-                                const float xa = acc[j][i][q * 4 + t] * rs * ga[t];
-                                const float xb = acc[j + 2][i][q * 4 + t] * rs * gb[t];
+                                const float xa = RADIX_ACC(j, i, q * 4 + t) * rs * ga[t];
+                                const float xb = RADIX_ACC(j + 2, i, q * 4 + t) * rs * gb[t];
                                 va[t] = (T)(xa * cs[t] - xb * sn[t]);
                                 vb[t] = (T)(xb * cs[t] + xa * sn[t]);
                             }
@@ -516,7 +585,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                         for (int q = 0; q < 4; ++q) {
                             V4 v;
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) v[t] = (T)acc[j][ip + il][q * 4 + t];
+                            for (int t = 0; t < 4; ++t) v[t] = (T)RADIX_ACC(j, ip + il, q * 4 + t);
                             *reinterpret_cast<V4*>(rowp + (j * 32 + 8 * q + 4 * g) * 2) = v;
                         }
                 }
@@ -532,12 +601,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
           }
         }
     }
+#undef RADIX_ACC
     }
 }
 
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
 int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out,
-               const QkvEpilogue& qe, hipStream_t stream) {
+               const QkvEpilogue& qe, const ARowMap& amap, const NormFusion& nf, hipStream_t stream) {
     typedef typename Op<DT>::T T;
     if (Nout % BN != 0 || K % (2 * BK) != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
@@ -546,13 +616,17 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     do {                                                                                                      \
         auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
         hipLaunchKernelGGL(kfn, grid, block, 0, stream, (const T*)A, (const T*)W, M, Nout, K, out, tiles_m,   \
-                           tiles_n, w_k, qe);                                                                 \
+                           tiles_n, w_k, qe, amap, nf);                                                       \
     } while (0)
     if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
     else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
     else if (epilogue == EPI_SWIGLU) RADIX_LAUNCH(EPI_SWIGLU);
     else if (epilogue == EPI_SWIGLU_SPLIT) RADIX_LAUNCH(EPI_SWIGLU_SPLIT);
     else if (epilogue == EPI_STORE_F32) RADIX_LAUNCH(EPI_STORE_F32);
+    else if (epilogue == EPI_RESIDUAL_NORM) {
+        if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_RESIDUAL_NORM);
+        else return RADIX_ERR_UNSUPPORTED;
+    }
     else if (epilogue == EPI_QKV_ROPE) {
         if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_QKV_ROPE);
         else return RADIX_ERR_UNSUPPORTED;
@@ -563,7 +637,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
 
 template <int DT>
 int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out, int variant,
-              const QkvEpilogue& qe, hipStream_t stream) {
+              const QkvEpilogue& qe, const ARowMap& amap, const NormFusion& nf, hipStream_t stream) {
     // Tile choice by a small cost model: workgroups run one per CU in rounds, a round costs a fixed part
     // (launch, first loads, epilogue) plus the k-tiles at the rate measured for that tile shape
     // (microseconds per 32-wide k-tile on MI355X, random fp16 operands): a launch that does not fill its
@@ -582,7 +656,7 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int
         double best = 0.0;
         for (const Shape& sh : shapes) {
             if (Nout % sh.bn != 0) continue;
-            if (epilogue == EPI_QKV_ROPE && sh.bn != 256) continue;      // needs 128-wide wavefront blocks
+            if ((epilogue == EPI_QKV_ROPE || epilogue == EPI_RESIDUAL_NORM) && sh.bn != 256) continue;   // need 128-wide wavefront blocks
             const double tiles = (double)ceil_div(M, sh.bm) * (Nout / sh.bn);
             double rounds = tiles / n_cu;
             if (rounds < 8.0) rounds = (double)(long long)(rounds + 0.999999);   // few rounds: the last one counts whole
@@ -591,15 +665,16 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int
         }
         if (variant == 0) return RADIX_ERR_UNSUPPORTED;
     }
-    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
-    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
-    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, stream);
+    if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
+    if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
+    return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
 }
 
 }  // namespace
 
 int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out, int op_dtype,
-                     int variant, hipStream_t stream, const QkvEpilogue* qkv, int w_k) {
+                     int variant, hipStream_t stream, const QkvEpilogue* qkv, int w_k, const ARowMap* a_rows,
+                     const NormFusion* norm) {
     if (M <= 0 || Nout <= 0) return RADIX_OK;
     if (K <= 0) return RADIX_ERR_UNSUPPORTED;
     if (w_k == 0) w_k = K;
@@ -610,7 +685,20 @@ int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int e
         if (!qkv || Nout % 256 != 0) return RADIX_ERR_UNSUPPORTED;
         qe = *qkv;
     }
-    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, stream);
-    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, stream);
+    ARowMap amap = {};
+    if (a_rows && a_rows->rows) {
+        // per-lane 32-bit byte offsets now span the whole source matrix
+        if (a_rows->n_src <= 0 || (long long)a_rows->n_src * K * 2 >= (1LL << 32)) return RADIX_ERR_UNSUPPORTED;
+        amap = *a_rows;
+    }
+    NormFusion nf = {};
+    if (norm) nf = *norm;
+    if (epilogue == EPI_RESIDUAL_NORM) {
+        if (Nout % 256 != 0 || !nf.a16 || !nf.gain || !nf.ss_out) return RADIX_ERR_UNSUPPORTED;
+        if ((((uintptr_t)nf.a16 | (uintptr_t)nf.gain) & 15) != 0) return RADIX_ERR_MISALIGNED;
+    }
+    if (nf.ss_in && (nf.n_slots_in <= 0 || nf.n_slots_in % 2 != 0 || ((uintptr_t)nf.ss_in & 7) != 0)) return RADIX_ERR_UNSUPPORTED;
+    if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, amap, nf, stream);
+    if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, amap, nf, stream);
     return RADIX_ERR_UNSUPPORTED;
 }

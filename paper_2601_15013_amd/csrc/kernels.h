@@ -52,6 +52,7 @@ enum GemmEpilogue {
     EPI_SWIGLU = 2,    // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
     EPI_QKV_ROPE = 3,  // EPI_STORE of the fused q|k|v row with per-head RMSNorm and RoPE applied to q and k heads
     EPI_STORE_F32 = 4, // C stored as fp32 (16-bit operand GEMMs only; the fp32 GEMM's EPI_STORE already is fp32)
+    EPI_RESIDUAL_NORM = 6, // EPI_RESIDUAL that also prepares the RMSNorm of the updated rows (NormFusion, producer side)
     EPI_SWIGLU_SPLIT = 5  // EPI_SWIGLU with the result y written as a 16-bit (hi, lo) pair: out[M, 2 (Nout/2)] holds
                           // T(y) in columns [0, Nout/2) and T(y - T(y)) in columns [Nout/2, Nout)
 };
@@ -65,13 +66,41 @@ struct QkvEpilogue {
     int n_q_heads, n_kv_heads, qk_norm;
     float eps;
 };
+// RMSNorm folded into the GEMMs on either side of it (paper: Algorithm 1, the "LayerNorm" lines in front of
+// "QKVProj" and "MLP"; read as RMSNorm).  y = x * rsqrt(mean(x^2) + eps) * g feeds a projection, and the row
+// scalar rsqrt(..) commutes with it, so:
+//   producer (EPI_RESIDUAL_NORM, the O / down projection that last updates the residual row x): besides
+//     resid += C it writes a16[m, :] = T(x[m, :] * gain[:]), the un-normalised operand of the next projection, and
+//     ss_out[m, s] = sum of x[m, c]^2 over the 128 columns c of slot s, summed in a fixed in-lane order that does
+//     not depend on M, on the tile shape or on where the row sits (every tile shape that may run this epilogue
+//     gives a wavefront exactly 128 columns);
+//   consumer (any 16-bit epilogue, ss_in != nullptr): row m of the product is multiplied by
+//     rsqrt(sum_s ss_in[m, s] * inv_d + eps) before the epilogue proper.
+struct NormFusion {
+    void* a16;            // producer: [M, Nout] in the operand type
+    const float* gain;    // producer: [Nout] gain of the norm that follows
+    float* ss_out;        // producer: [M, Nout / 128]
+    const float* ss_in;   // consumer: [M, n_slots_in] or nullptr
+    int n_slots_in;       // consumer: even
+    float inv_d, eps;     // consumer: 1 / (normalised width), epsilon inside the square root
+};
+
+// Optional row map of the A operand: row m of the product reads row rows[m] of A[n_src, K] for m < n_valid and row 0
+// beyond (Gather(t, I)[j] = t[I[j]] applied while loading); bad entries are clamped and recorded in *status.
+// Needs n_src * K * 2 < 2^32.
+struct ARowMap {
+    const int32_t* rows;
+    int n_valid, n_src;
+    int32_t* status;
+};
 void launch_gemm_f32(const float* A, const float* W, int M, int Nout, int K, int epilogue, float* out_or_resid,
                      hipStream_t stream);
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), fp32 accumulate.  variant 0 = pick a tile shape.
 // w_k: row length of W.  w_k == K is the plain product; w_k == K / 2 multiplies A = [hi | lo] against
 // the weights repeated twice along k, i.e. C = (hi + lo) * W^T.
 int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int epilogue, void* out_or_resid,
-                     int op_dtype, int variant, hipStream_t stream, const QkvEpilogue* qkv = nullptr, int w_k = 0);
+                     int op_dtype, int variant, hipStream_t stream, const QkvEpilogue* qkv = nullptr, int w_k = 0,
+                     const ARowMap* a_rows = nullptr, const NormFusion* norm = nullptr);
 
 // ---- causal varlen GQA attention on the full ragged layout.
 // qkv[N, dq + 2 dkv] rows hold q | k | v of one token; out[N, dq].
@@ -82,12 +111,39 @@ void launch_attention_f32(const float* qkv, const int32_t* cu, int B, int N, int
 int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                           int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out = 0);
 // The same attention with scatter and gather folded in: q | k | v rows are read from the COMPACT buffer
-// qkv_c[n_compact, dq + 2 dkv] through I_scatter, only the representative positions of a sequence
-// ([rep_start[b], len_b), see launch_rep_start) are computed, and their rows go straight to out_c[n_compact, dq].
+// qkv_c[n_compact, dq + 2 dkv] through I_scatter, only the representative positions of a sequence are computed,
+// and their rows go straight to out_c[n_compact, dq] (split_out: [n_compact, 2 dq], hi | lo).  The work list
+// comes from launch_attn_plan (same cu / I_scatter / n_q_heads / n_kv_heads).
 int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
-                                const int32_t* rep_start, int B, int N, int n_compact, int max_seqlen, int n_q_heads,
+                                const int32_t* plan, int B, int N, int n_compact, int n_q_heads,
                                 int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream,
                                 int split_out = 0);
-// rep_start[b] = first position of sequence b whose token is its own representative (len_b if none).
-void launch_rep_start(const int32_t* cu, const int32_t* I_scatter, const int32_t* I_gather, int B, int N,
-                      int n_compact, int32_t* rep_start, hipStream_t stream);
+
+// Work list of the fused attention kernel, built once per forward.  The representative positions of sequence
+// b are its tail [first_b, len_b) (first_b: the first position whose token is its own representative); they are
+// cut into blocks of 32 query rows.  A workgroup serves `slots` blocks (slots = 4 / min(group, 4) wavefronts per
+// query head): `slots` consecutive blocks of one sequence where a sequence has that many left, else the leftover
+// blocks of consecutive sequences packed together, which then share the K/V tiles of their common prefix.
+// Layout of plan[] (int32): [0] number of items, [1] number of single-sequence items; per-sequence scratch; per
+// item: t_shared (K/V tiles of 64 keys that all slots walk together; INT_MAX: all of them), seq[4], q[4]
+// (sequence and first query position of every slot, seq = -1: empty slot).
+struct AttnPlanLayout {
+    size_t first, lcp, nfull, nrem, t_shared, seq, q, total;   // offsets in int32 words
+    int max_items;
+};
+static inline AttnPlanLayout attn_plan_layout(size_t N, size_t B) {
+    AttnPlanLayout L;
+    L.max_items = (int)(N / 32 + B + 1);
+    size_t off = 4;
+    L.first = off; off += B;
+    L.lcp = off; off += B;
+    L.nfull = off; off += B;
+    L.nrem = off; off += B;
+    L.t_shared = off; off += (size_t)L.max_items;
+    L.seq = off; off += 4 * (size_t)L.max_items;
+    L.q = off; off += 4 * (size_t)L.max_items;
+    L.total = off;
+    return L;
+}
+void launch_attn_plan(const int32_t* cu, const int32_t* I_scatter, const int32_t* I_gather, int B, int N,
+                      int n_compact, int n_q_heads, int n_kv_heads, int32_t* plan, hipStream_t stream);

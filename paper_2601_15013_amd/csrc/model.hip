@@ -95,7 +95,7 @@ __global__ __launch_bounds__(1024) void sum_squares_bf16_kernel(const bf16_t* __
 size_t esize(int dtype) { return dtype == RADIX_F32 ? 4 : 2; }
 
 struct WsLayout {
-    size_t pos_full, ids_c, pos_c, rep_start, h, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
+    size_t pos_full, ids_c, pos_c, plan, h, ss, a, qkv, qkv_full, attn_full, attn_c, mlp, ynorm, total;
 };
 
 WsLayout ws_layout(const radix_model_config& c, int hilo_layers, size_t N, size_t B) {
@@ -109,8 +109,9 @@ WsLayout ws_layout(const radix_model_config& c, int hilo_layers, size_t N, size_
     L.pos_full = take(N * 4);
     L.ids_c = take(M * 4);
     L.pos_c = take(M * 4);
-    L.rep_start = take(B * 4);
+    L.plan = take(attn_plan_layout(N, B).total * 4);
     L.h = take(M * c.d * 4);
+    L.ss = take(M * ((size_t)c.d / 128 + 1) * 4);      // per-row sums of squares in 128-column slots (RMSNorm folded into the GEMMs)
     const size_t w2 = hilo_layers > 0 ? 2 : 1;     // (hi, lo) rows are twice as wide
     L.a = take(M * c.d * es * w2);
     L.qkv = take(M * row * es);
@@ -313,8 +314,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
                  int max_seqlen, const int32_t* Is, const int32_t* Ig, int M, bool dedup, bool fused, int pad_to,
                  float* out, void* ws, size_t ws_bytes, hipStream_t stream) {
     const radix_model_config& c = model->cfg;
-    if (fused && c.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;   // the fused kernel is the MFMA one
-    fused = fused && dedup;
+    fused = fused && dedup && c.compute_dtype != RADIX_F32;   // the fused kernel is the MFMA one
     // the fused kernel addresses the compact q|k|v buffer with 32-bit byte offsets; beyond 4 GB the three-kernel
     // path (same results) takes over
     if (fused && (long long)M * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * (long long)esize(c.compute_dtype) >= (1LL << 32))
@@ -333,8 +333,9 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     int32_t* pos_full = (int32_t*)(w + L.pos_full);
     int32_t* ids_c = (int32_t*)(w + L.ids_c);
     int32_t* pos_c = (int32_t*)(w + L.pos_c);
-    int32_t* rep_start = (int32_t*)(w + L.rep_start);
+    int32_t* plan = (int32_t*)(w + L.plan);
     float* h = (float*)(w + L.h);
+    float* ss = (float*)(w + L.ss);
     void* a = w + L.a;
     void* qkv = w + L.qkv;
     void* qkv_full = dedup ? (void*)(w + L.qkv_full) : qkv;
@@ -360,15 +361,24 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     }
     launch_compact_ids(tok, pos, dedup ? Ig : nullptr, M, M_valid, N, c.vocab, c.max_pos, ids_c, pos_c, hdr, stream);
     launch_embed(model->embed, c.dtype, ids_c, M, d, h, stream);
-    if (fused) launch_rep_start(cu, Is, Ig, B, N, M_valid, rep_start, stream);
+    if (fused) launch_attn_plan(cu, Is, Ig, B, N, M_valid, c.n_q_heads, c.n_kv_heads, plan, stream);
 
     // C = A W^T over K columns of A; w_k = row length of W (K, or K / 2 when A rows are (hi, lo) pairs)
     auto gemm = [&](const void* A, const void* W, int Nout, int K, int w_k, int epi, void* o,
-                    const QkvEpilogue* qe = nullptr) -> int {
-        if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream, qe, w_k);
+                    const QkvEpilogue* qe = nullptr, const ARowMap* amap = nullptr, const NormFusion* nf = nullptr) -> int {
+        if (dt != RADIX_F32) return launch_gemm_mfma(A, W, M, Nout, K, epi, o, dt, 0, stream, qe, w_k, amap, nf);
         launch_gemm_f32((const float*)A, (const float*)W, M, Nout, K, epi, (float*)o, stream);
         return RADIX_OK;
     };
+    // RMSNorm folded into the GEMMs around it (16-bit operands, d a multiple of 256, layers without (hi, lo) inputs):
+    // the projection that last updates the residual rows also writes T(x * gain) and the rows' sums of squares, and
+    // the projection that consumes the norm scales its rows by rsqrt(mean + eps).  `normed` says that `a` and `ss`
+    // already hold that for the norm about to run.
+    const bool can_fold = dt != RADIX_F32 && d % 256 == 0;
+    const int n_slots = d / 128;
+    bool normed = false;
+    NormFusion consume = {};
+    consume.ss_in = ss; consume.n_slots_in = n_slots; consume.inv_d = 1.0f / (float)d; consume.eps = c.eps;
 
     int rc = RADIX_OK;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -381,7 +391,8 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         // hold launches of one size only
         const int t_qkv = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_QKV, t_o = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_O;
         const int t_gu = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_GATEUP, t_dn = hl ? RADIX_TIME_GEMM_HILO : RADIX_TIME_GEMM_DOWN;
-        {
+        const bool folded1 = normed;            // the down projection of the layer before prepared this norm
+        if (!folded1) {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
             if (hl) {
                 if ((rc = launch_rmsnorm_split(h, Lw.g1, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
@@ -395,7 +406,8 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
             TimedScope t(t_qkv, stream);
             const QkvEpilogue qe = {Lw.gq, Lw.gk, model->cos_tab, model->sin_tab, pos_c,
                                     c.n_q_heads, c.n_kv_heads, c.qk_norm, c.eps};
-            rc = gemm(a, Lw.wqkv, row, w2 * d, d, fused_rope ? EPI_QKV_ROPE : EPI_STORE, qkv, fused_rope ? &qe : nullptr);
+            rc = gemm(a, Lw.wqkv, row, w2 * d, d, fused_rope ? EPI_QKV_ROPE : EPI_STORE, qkv, fused_rope ? &qe : nullptr,
+                      nullptr, folded1 ? &consume : nullptr);
             if (rc != RADIX_OK) return rc;
         }
         if (!fused_rope) {
@@ -406,8 +418,8 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         const size_t attn_row_bytes = (size_t)w2 * dq * es;
         if (fused) {   // scatter, attention and gather in one kernel (exact): compact rows in, compact rows out
             TimedScope t(RADIX_TIME_ATTENTION, stream);
-            rc = launch_attention_mfma_fused(qkv, cu, Is, rep_start, B, N, M_valid, max_seqlen, c.n_q_heads,
-                                             c.n_kv_heads, hd, attn_c, dt, stream, hl);
+            rc = launch_attention_mfma_fused(qkv, cu, Is, plan, B, N, M_valid, c.n_q_heads, c.n_kv_heads, hd, attn_c,
+                                             dt, stream, hl);
             if (rc != RADIX_OK) return rc;
             if (M > M_valid)    // padding rows: any defined value will do, they only feed rows nobody reads
                 launch_index_select_rows(attn_c, M_valid, nullptr, M - M_valid, attn_row_bytes,
@@ -428,15 +440,26 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
                                      (float*)attn_full, stream);
             }
         }
-        if (dedup && !fused) {   // Gather(a)
+        // Gather(a): with 16-bit operands the output projection reads its rows through I_gather itself (no copy);
+        // the fp32 GEMM, and a full-layout buffer too large for 32-bit row offsets, take the row copy
+        const bool gather_in_gemm = dedup && !fused && dt != RADIX_F32 && (long long)N * (long long)attn_row_bytes < (1LL << 32);
+        if (dedup && !fused && !gather_in_gemm) {
             TimedScope t(RADIX_TIME_GATHER, stream);
             launch_index_select_rows(attn_full, N, Ig, M, attn_row_bytes, attn_c, hdr, stream, M_valid);
         }
         {
             TimedScope t(t_o, stream);
-            if ((rc = gemm(attn_c, Lw.wo, d, w2 * dq, dq, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+            const ARowMap amap = {Ig, M_valid, N, hdr};
+            const bool fold2 = can_fold && !hl;     // this projection prepares the post-attention norm
+            NormFusion produce = {};
+            produce.a16 = a; produce.gain = Lw.g2; produce.ss_out = ss;
+            rc = gemm(gather_in_gemm ? attn_full : attn_c, Lw.wo, d, w2 * dq, dq, fold2 ? EPI_RESIDUAL_NORM : EPI_RESIDUAL, h,
+                      nullptr, gather_in_gemm ? &amap : nullptr, fold2 ? &produce : nullptr);
+            if (rc != RADIX_OK) return rc;
+            normed = fold2;
         }
-        {
+        const bool folded2 = normed;
+        if (!folded2) {
             TimedScope t(RADIX_TIME_ROWOPS, stream);
             if (hl) {
                 if ((rc = launch_rmsnorm_split(h, Lw.g2, M, d, c.eps, a, dt, stream)) != RADIX_OK) return rc;
@@ -446,11 +469,21 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         {
             TimedScope t(t_gu, stream);
-            if ((rc = gemm(a, Lw.wgu, 2 * c.d_int, w2 * d, d, hl ? EPI_SWIGLU_SPLIT : EPI_SWIGLU, mlp)) != RADIX_OK) return rc;
+            rc = gemm(a, Lw.wgu, 2 * c.d_int, w2 * d, d, hl ? EPI_SWIGLU_SPLIT : EPI_SWIGLU, mlp, nullptr, nullptr,
+                      folded2 ? &consume : nullptr);
+            if (rc != RADIX_OK) return rc;
         }
         {
             TimedScope t(t_dn, stream);
-            if ((rc = gemm(mlp, Lw.wd, d, w2 * c.d_int, c.d_int, EPI_RESIDUAL, h)) != RADIX_OK) return rc;
+            // prepares the pre-attention norm of the next layer, unless that layer takes (hi, lo) inputs or there is none
+            const bool fold1 = can_fold && l + 1 < c.n_layers && l + 1 >= model->hilo_layers;
+            NormFusion produce = {};
+            produce.a16 = a; produce.ss_out = ss;
+            if (fold1) produce.gain = model->layers[l + 1].g1;
+            rc = gemm(mlp, Lw.wd, d, w2 * c.d_int, c.d_int, fold1 ? EPI_RESIDUAL_NORM : EPI_RESIDUAL, h, nullptr, nullptr,
+                      fold1 ? &produce : nullptr);
+            if (rc != RADIX_OK) return rc;
+            normed = fold1;
         }
     }
     if (dedup) {
@@ -484,11 +517,28 @@ extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* to
     if (rc != RADIX_OK) return rc;
     if (n_compact < 0 || n_compact > N || (N > 0 && n_compact == 0)) return RADIX_ERR_BAD_SIZE;
     if (N > 0 && (!I_scatter || !I_gather)) return RADIX_ERR_NULL_POINTER;
-    const float threshold = opts ? opts->threshold : 1.0f;
+    const int mode = opts ? opts->attention_mode : RADIX_ATTN_AUTO;
+    if (mode != RADIX_ATTN_AUTO && mode != RADIX_ATTN_THREE_KERNELS && mode != RADIX_ATTN_FUSED) return RADIX_ERR_BAD_CONFIG;
+    if (mode == RADIX_ATTN_FUSED && model->cfg.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;
+    const bool fused = mode == RADIX_ATTN_FUSED || (mode == RADIX_ATTN_AUTO && model->cfg.compute_dtype != RADIX_F32);
+    const float threshold = opts ? opts->threshold : RADIX_THRESHOLD_AUTO;
     const bool force = opts ? opts->force_dedup != 0 : false;
-    const bool dedup = force || ((double)n_compact < (double)threshold * (double)N);
-    const bool fused = opts ? opts->fused_attention != 0 : false;
-    if (opts && opts->fused_attention != 0 && opts->fused_attention != 1) return RADIX_ERR_BAD_CONFIG;
+    bool dedup;
+    if (force) {
+        dedup = true;
+    } else if (threshold >= 0.f) {
+        dedup = (double)n_compact < (double)threshold * (double)N;
+    } else if (fused) {
+        dedup = n_compact < N;                  // nothing to lose: no [N, .] copies, no attention on duplicate rows
+    } else {
+        // three-kernel attention: the scatter's bytes against the position-wise flops of the rows saved
+        const radix_model_config& c = model->cfg;
+        const double dq = (double)c.n_q_heads * c.head_dim, dkv = (double)c.n_kv_heads * c.head_dim;
+        const double flops_row = 2.0 * c.d * (dq + 2 * dkv) + 2.0 * dq * c.d + 6.0 * (double)c.d * c.d_int;
+        const double row_bytes = (dq + 2 * dkv) * (double)esize(c.compute_dtype);
+        const double gemm_rate = c.compute_dtype == RADIX_F32 ? 2.0e13 : 1.1e15, copy_rate = 5.0e12;
+        dedup = ((double)N - n_compact) * flops_row / gemm_rate > ((double)N + n_compact) * row_bytes / copy_rate;
+    }
     if (opts && opts->pad_compact_to < 0) return RADIX_ERR_BAD_CONFIG;
     const int pad_to = opts ? opts->pad_compact_to : 0;
     if (!dedup) n_compact = N;

@@ -253,17 +253,26 @@ void launch_rows_to_operand(const float* src, int n_src, const int32_t* sel, int
         hipLaunchKernelGGL(rows_to_operand_kernel<f16_t>, grid, block, 0, stream, src, n_src, sel, n_rows, d, (f16_t*)out, status);
 }
 
-// First representative position of every sequence: the smallest p with I_gather[I_scatter[start + p]] ==
-// start + p, or len if the whole sequence duplicates earlier ones.  In a trie the predicate is monotone
-// along a sequence (a token that opens a new node makes every later token of the sequence open one
-// too), so a binary search finds it.  Map entries are clamped; a malformed map cannot fault.
-__global__ void rep_start_kernel(const int32_t* __restrict__ cu, const int32_t* __restrict__ Is,
-                                 const int32_t* __restrict__ Ig, int B, int N, int M, int32_t* __restrict__ rep) {
+// ---------------------------------------------------------------- work list of the fused attention kernel
+// Per sequence: first representative position (the smallest p with I_gather[I_scatter[start + p]] == start + p,
+// or len if the whole sequence duplicates earlier ones; in a trie the predicate is monotone along a sequence - a
+// token that opens a new node makes every later token of the sequence open one too - so a binary search finds
+// it), the length of the prefix it shares with the sequence before it (compact rows equal, then different: monotone
+// as well), and how many 32-row blocks of representative positions go into single-sequence items / are left over.
+// Map entries are clamped; a malformed map cannot fault.
+__global__ void attn_seq_stats_kernel(const int32_t* __restrict__ cu, const int32_t* __restrict__ Is,
+                                      const int32_t* __restrict__ Ig, int B, int N, int M, int slots,
+                                      int32_t* __restrict__ first, int32_t* __restrict__ lcp,
+                                      int32_t* __restrict__ nfull, int32_t* __restrict__ nrem) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    int start = cu[b], end = cu[b + 1];
-    start = start < 0 ? 0 : (start > N ? N : start);
-    end = end < start ? start : (end > N ? N : end);
+    auto bounds = [&](int s, int& start, int& end) {
+        start = cu[s]; end = cu[s + 1];
+        start = start < 0 ? 0 : (start > N ? N : start);
+        end = end < start ? start : (end > N ? N : end);
+    };
+    int start, end;
+    bounds(b, start, end);
     int lo = 0, hi = end - start;
     while (lo < hi) {
         const int mid = (lo + hi) >> 1;
@@ -271,13 +280,114 @@ __global__ void rep_start_kernel(const int32_t* __restrict__ cu, const int32_t* 
         c = c < 0 ? 0 : (c >= M ? M - 1 : c);
         if (Ig[c] == start + mid) hi = mid; else lo = mid + 1;
     }
-    rep[b] = lo;
+    first[b] = lo;
+    const int blocks = (end - start - lo + 31) / 32;
+    nfull[b] = blocks / slots;
+    nrem[b] = blocks % slots;
+    int common = 0;
+    if (b > 0) {
+        int ps, pe;
+        bounds(b - 1, ps, pe);
+        int l2 = 0, h2 = (pe - ps) < (end - start) ? (pe - ps) : (end - start);
+        while (l2 < h2) {
+            const int mid = (l2 + h2) >> 1;
+            if (Is[ps + mid] != Is[start + mid]) h2 = mid; else l2 = mid + 1;
+        }
+        common = l2;
+    }
+    lcp[b] = common;
 }
 
-void launch_rep_start(const int32_t* cu, const int32_t* Is, const int32_t* Ig, int B, int N, int M, int32_t* rep,
-                      hipStream_t stream) {
+// One workgroup: exclusive scans of the two block counts over the sequences, then the item records.
+__global__ __launch_bounds__(1024) void attn_plan_kernel(int B, int slots, int max_items, int32_t* __restrict__ plan,
+                                                         const int32_t* __restrict__ first,
+                                                         const int32_t* __restrict__ lcp, int32_t* nfull,
+                                                         int32_t* nrem, int32_t* __restrict__ t_shared,
+                                                         int32_t* __restrict__ seq, int32_t* __restrict__ q) {
+    __shared__ int wave_tot[2][16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int run_f = 0, run_r = 0;
+    for (int base = 0; base < B; base += 1024) {
+        const int s = base + tid;
+        const int cf = s < B ? nfull[s] : 0, cr = s < B ? nrem[s] : 0;
+        int inf = cf, inr = cr;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int vf = __shfl_up(inf, o, 64), vr = __shfl_up(inr, o, 64);
+            if (lane >= o) { inf += vf; inr += vr; }
+        }
+        if (lane == 63) { wave_tot[0][wave] = inf; wave_tot[1][wave] = inr; }
+        __syncthreads();
+        int bf = 0, br = 0, tf = 0, tr = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int vf = wave_tot[0][w], vr = wave_tot[1][w];
+            if (w < wave) { bf += vf; br += vr; }
+            tf += vf; tr += vr;
+        }
+        if (s < B) { nfull[s] = run_f + bf + inf - cf; nrem[s] = run_r + br + inr - cr; }   // now exclusive bases
+        run_f += tf; run_r += tr;
+        __syncthreads();
+    }
+    const int n_reg = run_f, n_left = run_r;
+    const int n_packed = (n_left + slots - 1) / slots;
+    const int n_items = n_reg + n_packed <= max_items ? n_reg + n_packed : max_items;   // cannot exceed it; keeps writes inside
+    if (tid == 0) { plan[0] = n_items; plan[1] = n_reg; }
+    // records.  Sequence s: its first (leftover) blocks go to the packed items, the rest `slots` at a time.
+    for (int s = tid; s < B; s += 1024) {
+        const int fb = nfull[s], lb = nrem[s];
+        const int cf = (s + 1 < B ? nfull[s + 1] : n_reg) - fb, cr = (s + 1 < B ? nrem[s + 1] : n_left) - lb;
+        const int f = first[s];
+        for (int i = 0; i < cr; ++i) {
+            const int L = lb + i, item = n_reg + L / slots;
+            if (item < max_items) { seq[4 * item + L % slots] = s; q[4 * item + L % slots] = f + 32 * i; }
+        }
+        for (int k = 0; k < cf; ++k) {
+            const int item = fb + k;
+            if (item >= max_items) break;
+            t_shared[item] = 0x7FFFFFFF;
+            for (int w = 0; w < 4; ++w) {
+                seq[4 * item + w] = w < slots ? s : -1;
+                q[4 * item + w] = f + 32 * (cr + k * slots + w);
+            }
+        }
+    }
+    for (int L = n_left + tid; L < n_packed * slots; L += 1024) {       // empty slots of the last packed item
+        const int item = n_reg + L / slots;
+        if (item < max_items) { seq[4 * item + L % slots] = -1; q[4 * item + L % slots] = 0; }
+    }
+    __syncthreads();
+    // packed items: all slots walk together the K/V tiles below the prefix they share (and below every slot's
+    // first query, so that the tiles carry no causal boundary of their own)
+    for (int g = tid; g < n_packed; g += 1024) {
+        const int item = n_reg + g;
+        if (item >= max_items) break;
+        for (int w = slots; w < 4; ++w) { seq[4 * item + w] = -1; q[4 * item + w] = 0; }
+        int common = 0x7FFFFFFF, prev = -1;
+        for (int w = 0; w < slots; ++w) {
+            const int s = seq[4 * item + w];
+            if (s < 0) continue;
+            const int qs = q[4 * item + w];
+            common = qs < common ? qs : common;
+            if (prev >= 0)
+                for (int x = prev + 1; x <= s; ++x) common = lcp[x] < common ? lcp[x] : common;
+            prev = s;
+        }
+        t_shared[item] = common == 0x7FFFFFFF ? 0 : common / 64;
+    }
+}
+
+void launch_attn_plan(const int32_t* cu, const int32_t* Is, const int32_t* Ig, int B, int N, int M, int n_q_heads,
+                      int n_kv_heads, int32_t* plan, hipStream_t stream) {
     if (B <= 0 || M <= 0) return;
-    hipLaunchKernelGGL(rep_start_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, stream, cu, Is, Ig, B, N, M, rep);
+    const int group = n_q_heads / n_kv_heads;
+    const int hpb = (group % 4 == 0) ? 4 : (group % 2 == 0 ? 2 : 1);
+    const int slots = 4 / hpb;
+    const AttnPlanLayout L = attn_plan_layout((size_t)N, (size_t)B);
+    hipLaunchKernelGGL(attn_seq_stats_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, stream, cu, Is, Ig, B, N, M, slots,
+                       plan + L.first, plan + L.lcp, plan + L.nfull, plan + L.nrem);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, stream, B, slots, L.max_items, plan, plan + L.first,
+                       plan + L.lcp, plan + L.nfull, plan + L.nrem, plan + L.t_shared, plan + L.seq, plan + L.q);
 }
 
 void launch_validate_cu(const int32_t* cu, int B, int N, int max_seqlen, int32_t* status, hipStream_t stream) {

@@ -69,6 +69,7 @@ def test_forward_rejects_bad_host_arguments(lib):
     assert g(None, fake, None, fake, 1, 4, 4, fake, fake, 1 << 20, None) == -1
     n = C.c_size_t()
     assert lib.radix_workspace_bytes(None, 4, 1, C.byref(n)) == -1
+    assert lib.radix_model_hilo_layers(None) == -1
 
 
 def test_model_create_rejects_bad_config(lib):

@@ -119,7 +119,7 @@ def test_hilo_layers_tighten_the_error():
     w = synth.SynthWeights(SMALL_BF16, 31)
     ref = U.oracle_rows(w, b)
     for hilo in (-1, 1, 3):     # none, the first layer, all three layers
-        y, y_nd, _ = run_all(w, b, compute="bf16", hilo=hilo)
+        y, y_nd, _ = run_all(w, b, compute="bf16", hilo=hilo, fused_attention=False)
         y_f, _, _ = run_all(w, b, compute="bf16", hilo=hilo, fused_attention=True)
         errs[hilo] = U.rms_err(y, ref)
         assert np.array_equal(y, y_nd) and np.array_equal(y, y_f)
@@ -131,6 +131,26 @@ def test_hilo_layers_tighten_the_error():
     e3 = U.rms_err(run_all(w, b, hilo=3)[0], ref)
     print("fp16 operands, relative RMS error with (hi, lo) inputs in no / all layers:", e0, e3)
     assert e3 < e0
+
+
+@pytest.mark.parametrize("compute", ["f16", "bf16"])
+@pytest.mark.parametrize("qk_norm", [True, False])
+def test_16bit_qkv_row_of_640_takes_the_unfused_qknorm_rope_kernel(compute, qk_norm):
+    # 3 Q heads + 1 KV head of 128: the fused q|k|v row is 640 = 5 x 128 wide, not a multiple of the 256-column GEMM
+    # tile whose epilogue applies Q/K-norm + RoPE, so the projection stores plain rows and the row kernel
+    # normalises and rotates them in place in the 16-bit operand type
+    # (d = 384 is not a multiple of 256 either: the RMSNorms run as kernels of their own instead of inside the GEMMs)
+    cfg = synth.ModelConfig("bf16q", 2, 384, 3, 1, 128, 320, 1500, "bf16", max_pos=512, qk_norm=qk_norm)
+    w = synth.SynthWeights(cfg, 37)
+    b = synth.multilevel_batch(9, 9, 70, 3, 20, 1, 200, cfg.vocab)
+    ref = U.oracle_rows(w, b)
+    for fused in (False, True):
+        y, y_nd, n_c = run_all(w, b, compute=compute, hilo=-1, fused_attention=fused)
+        assert n_c == b.expected_n_compact
+        e = U.rel_err(y, ref)
+        print(f"row 640, {compute} operands, qk_norm={qk_norm}, fused attention={fused}: err {e:.3e}")
+        assert e <= (TOL_BF16 if compute == "f16" else 5e-2)       # bf16 operands: sanity bound only
+        assert np.array_equal(y, y_nd)
 
 
 def test_bf16_wide_model_uses_large_gemm_tiles():
@@ -242,6 +262,26 @@ def test_c5_full_size_sampled_sequences():
 def test_c5_control_batch_no_sharing():
     # same token count, nothing shared, deduplication forced on: identity maps, M = N
     _sampled_parity("C5ctl", [3, 40, 77, 120])
+
+
+def test_sweep_point_0_6b_prefix_128_suffix_256():
+    # one row of the paper's forward-pass sweep (B = 32, one shared prefix + distinct fixed-length suffixes), as
+    # bench.py --workload SWEEPTABLE builds it: 12 288 tokens -> 8 320 rows, both attention modes
+    cfg = synth.QWEN3_0_6B
+    b = synth.shared_prefix_batch(2001, 32, 128, 256, 256, cfg.vocab, name="sweep")
+    w = synth.SynthWeights(cfg, 2001)
+    assert (b.N, b.expected_n_compact) == (12288, 8320)
+    seqs = [0, 11, 22, 31]
+    rows = U.rows_of(b, seqs)
+    ref = U.oracle_rows(w, b, sequences=seqs)
+    f = U.tail_factor(ref.size, b.N * cfg.d)
+    for fused in (None, False):
+        y, y_nd, n_c = run_all(w, b, fused_attention=fused)
+        assert n_c == 8320
+        e = U.rel_err(y[rows], ref)
+        print(f"sweep 0.6B 128/256, fused_attention={fused}: max err {e:.3e} rms {U.rms_err(y[rows], ref):.3e} x{f:.3f}")
+        assert e * f <= TOL_BF16
+        assert np.array_equal(y, y_nd)
 
 
 def test_padding_of_the_compact_space_changes_nothing():

@@ -23,7 +23,8 @@ def run_modes(weights, batch, pos=None):
         tok, cu = harness.upload_batch(batch)
         pos_t = None if pos is None else torch.from_numpy(np.asarray(pos, dtype=np.int32)).cuda()
         maps = run.build_index(tok, cu, pos_t)
-        y = run.forward(tok, cu, batch.max_seqlen, maps, pos=pos_t, force_dedup=True).cpu().numpy()
+        y = run.forward(tok, cu, batch.max_seqlen, maps, pos=pos_t, force_dedup=True,
+                        fused_attention=False).cpu().numpy()
         assert run.status() == 0
         y_f = run.forward(tok, cu, batch.max_seqlen, maps, pos=pos_t, force_dedup=True,
                           fused_attention=True).cpu().numpy()
@@ -51,6 +52,26 @@ def test_fused_ragged_multilevel_several_tiles_explicit_positions():
     assert n_c == b.expected_n_compact
     assert np.array_equal(y, y_f)
     assert U.rel_err(y_f, U.oracle_rows(w, b, pos=pos)) <= TOL_BF16
+
+
+@pytest.mark.parametrize("heads", [(4, 2), (2, 2), (8, 2)])
+def test_fused_short_suffixes_of_different_sequences_share_a_workgroup(heads):
+    # Suffixes of at most 32 representative rows behind long shared prefixes: with 2 (or 4) row slots per workgroup
+    # the leftover blocks of consecutive sequences are packed together and walk the common prefix's K/V tiles
+    # once.  (4, 2): two slots; (2, 2): four slots, one head per workgroup; (8, 2): one slot, nothing to pack.
+    hq, hkv = heads
+    cfg = synth.ModelConfig("bf16p", 2, 256, hq, hkv, 128, 320, 2000, "bf16", max_pos=1024)
+    w = synth.SynthWeights(cfg, 45)
+    # three-level trie: 200 shared, 4 groups x 70, then suffixes of 1..40 tokens (some sequences one block, some two,
+    # first query positions not tile-aligned); and a flat one with empty and one-token suffixes
+    deep = synth.multilevel_batch(10, 24, 200, 4, 70, 1, 40, cfg.vocab)
+    flat = synth.shared_prefix_batch(11, 13, 333, 0, 32, cfg.vocab)
+    mixed = synth.multilevel_batch(12, 10, 130, 5, 3, 20, 110, cfg.vocab)      # 1 to 4 blocks per sequence
+    for b in (deep, flat, mixed):
+        y, y_f, n_c = run_modes(w, b)
+        assert n_c == b.expected_n_compact
+        assert np.array_equal(y, y_f), b.name
+        assert U.rel_err(y_f, U.oracle_rows(w, b)) <= TOL_BF16
 
 
 def test_fused_whole_sequences_duplicated_and_tiny_batches():
