@@ -76,6 +76,8 @@ def main() -> int:
     ap.add_argument("--hilo-layers", type=int, default=0,
                     help="radix_model_config.hilo_layers: 0 = decided by the library from the weights (what the parity "
                          "tests run with), k > 0 = the first k layers, -1 = none")
+    ap.add_argument("--fold-norms", action="store_true",
+                    help="radix_model_config.fold_norms = 1: RMSNorms folded into the GEMMs around them (default: norm kernels)")
     ap.add_argument("--sweep-model", choices=["0.6B", "4B", "8B"], default="0.6B", help="--workload SWEEP: model shape")
     ap.add_argument("--sweep-prefix", type=int, default=2048, help="--workload SWEEP: shared prefix length")
     ap.add_argument("--sweep-suffix", type=int, default=256, help="--workload SWEEP: suffix length")
@@ -116,7 +118,8 @@ def main() -> int:
         batch = synth.make_batch(key)
         weights = synth.make_weights(key)
     cfg = weights.cfg
-    model = harness.upload_model(weights, hilo_layers=args.hilo_layers, lm_head_mode=1 if args.lm_head else 0)
+    model = harness.upload_model(weights, hilo_layers=args.hilo_layers, lm_head_mode=1 if args.lm_head else 0,
+                                 fold_norms=int(args.fold_norms))
     compute_dtype, hilo = model.compute_dtype, model.hilo_layers
     run = harness.Runner(model, batch.N, batch.B)
     tok, cu = harness.upload_batch(batch)
@@ -221,7 +224,7 @@ def main() -> int:
                                                      f"suffix {args.sweep_suffix}" if key == "SWEEP" else ""), "B": B, "N": N, "N_compact": n_c,
                    "compression_r": N / max(n_c, 1), "layers": cfg.n_layers, "seed": SWEEP_SEED if key == "SWEEP" else synth.WORKLOADS[key].seed,
                    "weights": cfg.dtype, "operands": compute_dtype, "accumulate": "f32",
-                   "hilo_layers": hilo,
+                   "hilo_layers": hilo, "fold_norms": int(args.fold_norms),
                    "attention_mode": "fused (indexed q/k/v, representative rows only)" if fused
                    else "scatter -> attention over N rows -> gather"},
         "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
@@ -311,7 +314,7 @@ def sweep_table_bench(args, torch, np, binding, harness, synth):
     Timings exclude the index build, as the paper's do."""
     model_cfg = {"0.6B": synth.QWEN3_0_6B, "4B": synth.QWEN3_4B, "8B": synth.QWEN3_8B}[args.sweep_model]
     weights = synth.SynthWeights(model_cfg, SWEEP_SEED)
-    model = harness.upload_model(weights, hilo_layers=args.hilo_layers)
+    model = harness.upload_model(weights, hilo_layers=args.hilo_layers, fold_norms=int(args.fold_norms))
     n_max = max(32 * (p + s) for p, s in SWEEP_ROWS)
     run = harness.Runner(model, n_max, 32)
     out = torch.empty((n_max, model_cfg.d), dtype=torch.float32, device="cuda")

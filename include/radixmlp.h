@@ -74,6 +74,14 @@ typedef struct radix_model_config {
                             0: decided from the weights at create time: RADIX_HILO_AUTO_LAYERS layers when
                                rms(Wq of layer 0) * sqrt(d) >= RADIX_HILO_AUTO_GAIN, else none;
                             k > 0: the first min(k, n_layers) layers;  -1: none. */
+    int32_t fold_norms;  /* 1: fold every RMSNorm that sits between two 16-bit GEMMs into them (bf16 weights, d a multiple of
+                            256, layers without (hi, lo) inputs): the O / down projection that last updates a residual row
+                            also writes that row times the next norm's gain in the operand type and the row's sums of
+                            squares, and the projection that follows scales its output rows by rsqrt(mean + eps); two
+                            launches fewer per layer, same error.  0 (default): the norms run as kernels of their own,
+                            which is what measures faster on an MI355X (the 16-bit write stays either way, the saved
+                            fp32 read is worth less than what the longer GEMM epilogues and prologues cost: one
+                            workgroup per compute unit, nothing overlaps them). */
     int32_t lm_head;     /* 0: no LM head (radix_lm_head returns RADIX_ERR_UNSUPPORTED); 1: head tied to the embedding
                             matrix; 2: separate matrix radix_weights.lm_head.  Non-zero makes radix_model_create
                             keep the head in the operand type (a converted copy of the embedding when that

@@ -39,7 +39,7 @@ class RadixError(RuntimeError):
 
 class radix_model_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d", "n_q_heads", "n_kv_heads", "head_dim", "d_int", "vocab",
-                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "hilo_layers", "lm_head")] + [("eps", C.c_float), ("rope_base", C.c_float)]
+                                          "max_pos", "qk_norm", "dtype", "compute_dtype", "hilo_layers", "fold_norms", "lm_head")] + [("eps", C.c_float), ("rope_base", C.c_float)]
 
 
 class radix_layer_weights(C.Structure):
@@ -155,21 +155,22 @@ def default_compute_dtype(weight_dtype: str) -> str:
 
 
 def make_config(cfg: Any, compute_dtype: Optional[str] = None, hilo_layers: int = 0,
-                lm_head: int = 0) -> radix_model_config:
+                lm_head: int = 0, fold_norms: int = 0) -> radix_model_config:
     """cfg: any object with the shape attributes (n_layers, d, n_q_heads, ..., dtype).  The library-side
     settings are arguments of their own: compute_dtype ("f32" / "f16" / "bf16"; None = the default for the
     weight type), hilo_layers and lm_head as in radixmlp.h."""
     compute = compute_dtype or default_compute_dtype(cfg.dtype)
     return radix_model_config(cfg.n_layers, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_int, cfg.vocab,
                               cfg.max_pos, int(cfg.qk_norm), _DTYPES[cfg.dtype], _DTYPES[compute],
-                              int(hilo_layers), int(lm_head), cfg.eps, cfg.rope_base)
+                              int(hilo_layers), int(fold_norms), int(lm_head), cfg.eps, cfg.rope_base)
 
 
 def radix_model_create(cfg: Any, embed: torch.Tensor, gf: torch.Tensor,
                        layers: Sequence[Mapping[str, torch.Tensor]], lm_head: Optional[torch.Tensor] = None,
-                       compute_dtype: Optional[str] = None, hilo_layers: int = 0, lm_head_mode: int = 0) -> Model:
+                       compute_dtype: Optional[str] = None, hilo_layers: int = 0, lm_head_mode: int = 0,
+                       fold_norms: int = 0) -> Model:
     """embed/gf/layers/lm_head: CUDA tensors ([out, in] matrices in the config dtype, fp32 gains)."""
-    c = make_config(cfg, compute_dtype, hilo_layers, lm_head_mode)
+    c = make_config(cfg, compute_dtype, hilo_layers, lm_head_mode, fold_norms)
     arr = (radix_layer_weights * len(layers))()
     for l, lw in enumerate(layers):
         for name, _ in radix_layer_weights._fields_:

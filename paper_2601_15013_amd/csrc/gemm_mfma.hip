@@ -173,6 +173,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         }
     }
 
+    // RMSNorm folded in (consumer side): the first 16 sum-of-squares slots of every row this lane owns are
+    // requested here, ahead of the first tile loads, and added up once those are under way; the row scales
+    // then sit in MB registers through the main loop (the epilogue would otherwise start with a chain of
+    // dependent loads per tile).
+    constexpr bool CONSUMES_NORM = EPI != EPI_RESIDUAL && EPI != EPI_RESIDUAL_NORM && EPI != EPI_STORE_F32;
+    constexpr int SS_EARLY = 8;                                 // float2 loads per row requested early
+    float2 ssv[MB][SS_EARLY];
+    const bool scale_rows = CONSUMES_NORM && nf.ss_in != nullptr;
+    if (scale_rows) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            int gm = m0 + wm * WTM + i * 32 + r;
+            gm = gm < M ? gm : M - 1;
+            const float* sp = nf.ss_in + (size_t)gm * nf.n_slots_in;
+#pragma unroll
+            for (int u = 0; u < SS_EARLY; ++u)
+                ssv[i][u] = 2 * u < nf.n_slots_in ? *reinterpret_cast<const float2*>(sp + 2 * u) : make_float2(0.f, 0.f);
+        }
+    }
+
     // ---- LDS addressing.  The ring has five stages of STAGE_B bytes; tile t lives in stage t % 5.
     // Stage byte offsets are wave-uniform scalars that rotate as the loop advances, everything
     // lane-dependent is computed once: per k-step ks the byte offset of this lane's chunk in tile row
@@ -242,6 +262,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int UNITS = MB + NB;
     constexpr int HALF = MB * NB / 2;      // the reads ride on the first half of a k-step's MFMAs
     static_assert(UNITS >= A_LOADS && UNITS >= B_LOADS, "at most one pair of global->LDS loads per slice");
+    // row scales from the sums of squares: slots in increasing order (the early ones, then the rest); adding the
+    // zeros that stand in for slots a narrow model does not have changes nothing
+    float rsr[MB];
+#define RADIX_ROW_SCALES()                                                                                         \
+    do {                                                                                                           \
+        _Pragma("unroll") for (int i = 0; i < MB; ++i) rsr[i] = 1.0f;                                              \
+        if (scale_rows) {                                                                                          \
+            _Pragma("unroll") for (int i = 0; i < MB; ++i) {                                                       \
+                float ssum = 0.f;                                                                                  \
+                _Pragma("unroll") for (int u = 0; u < SS_EARLY; ++u) { ssum += ssv[i][u].x; ssum += ssv[i][u].y; } \
+                if (nf.n_slots_in > 2 * SS_EARLY) {                                                                \
+                    int gm = m0 + wm * WTM + i * 32 + r;                                                           \
+                    gm = gm < M ? gm : M - 1;                                                                      \
+                    const float* sp = nf.ss_in + (size_t)gm * nf.n_slots_in;                                       \
+                    for (int k0 = 2 * SS_EARLY; k0 < nf.n_slots_in; k0 += 2 * SS_EARLY) {                          \
+                        float2 more[SS_EARLY];                                                                     \
+                        _Pragma("unroll") for (int u = 0; u < SS_EARLY; ++u)                                       \
+                            more[u] = k0 + 2 * u < nf.n_slots_in ? *reinterpret_cast<const float2*>(sp + k0 + 2 * u) \
+                                                                 : make_float2(0.f, 0.f);                          \
+                        _Pragma("unroll") for (int u = 0; u < SS_EARLY; ++u) { ssum += more[u].x; ssum += more[u].y; } \
+                    }                                                                                              \
+                }                                                                                                  \
+                rsr[i] = 1.0f / sqrtf(ssum * nf.inv_d + nf.eps);                                                   \
+            }                                                                                                      \
+        }                                                                                                          \
+    } while (0)
     V8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
     if constexpr (NS == 5) {
     RADIX_ISSUE2(0, 0u, STAGE_B);
@@ -257,6 +303,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
+    RADIX_ROW_SCALES();
 
     // One k-tile = two k-steps of 16, software-pipelined over two fragment register sets and
     // scheduled by hand (the scheduling barriers pin the order): the first half of a k-step's MFMAs
@@ -342,6 +389,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) RADIX_FRAG1(0u, 0, fa0, fb0, u);
+    RADIX_ROW_SCALES();
     uint32_t so_e = 0, so_n = 2 * STAGE_B, so_w = 4 * STAGE_B;      // stages of t, t+2, t+4 (pairs are adjacent)
     for (int kt = 0; kt < KT; kt += 2) {
         const int kw = kt + 4 < KT ? kt + 4 : KT - 2;
@@ -395,6 +443,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         so_w = so_w + 2 * STAGE_B == 6 * STAGE_B ? 0u : so_w + 2 * STAGE_B;
     }
     }
+#undef RADIX_ROW_SCALES
 #undef RADIX_HALF0
 #undef RADIX_ISSUE2
 #undef RADIX_MFMA_RANGE
@@ -420,61 +469,59 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     const int lane = lane_opaque;
     const int r = lane & 31, g = lane >> 5;
 
-    // RMSNorm folded in (consumer side): row scale of every row this lane owns
-    float rsr[MB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i) rsr[i] = 1.0f;
-    if (EPI != EPI_RESIDUAL && EPI != EPI_RESIDUAL_NORM && EPI != EPI_STORE_F32 && nf.ss_in != nullptr) {
-#pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            int gm = m0 + wm * WTM + i * 32 + r;
-            gm = gm < M ? gm : M - 1;
-            const float* sp = nf.ss_in + (size_t)gm * nf.n_slots_in;
-            float ssum = 0.f;
-            for (int k = 0; k < nf.n_slots_in; k += 2) {         // fixed order: slot 0, 1, 2, ...
-                const float2 v = *reinterpret_cast<const float2*>(sp + k);
-                ssum += v.x;
-                ssum += v.y;
-            }
-            rsr[i] = 1.0f / sqrtf(ssum * nf.inv_d + nf.eps);
-        }
-    }
 #define RADIX_ACC(J, I, E) (acc[J][I][E] * rsr[I])
 
     if (EPI == EPI_RESIDUAL_NORM) {
         // fp32 read-modify-write of the residual stream as below, plus, per row: the updated values times the
         // gain of the norm that follows, in the operand type (what the next projection multiplies), and the
         // sum of their squares over this wavefront's 128 columns (in-lane in (j, q, t) order, then the partner
-        // lane that holds the other half of the row's columns)
+        // lane that holds the other half of the row's columns).  The loads of a row block are all issued before
+        // anything of the block before it is stored: written in that order by hand, because with three
+        // unrelated pointers in play the compiler may not move a load above a store on its own, and every
+        // (load, add, store) step would then pay the memory latency in turn.
         const int slot = (n0 + wn * WTN) >> 7, n_slots = Nout >> 7;
+        const float* grow = nf.gain + n0 + wn * WTN;
+        f32x4 gn[NB * 4];
+#pragma unroll
+        for (int jq = 0; jq < NB * 4; ++jq)
+            gn[jq] = *reinterpret_cast<const f32x4*>(grow + (jq >> 2) * 32 + 8 * (jq & 3) + 4 * g);
+        f32x4 cur[NB * 4], nxt[NB * 4];
+        auto load_block = [&](int i, f32x4* v) {
+            const int gm = m0 + wm * WTM + i * 32 + r;
+            const float* orow = (const float*)out_ + (size_t)(gm < M ? gm : M - 1) * Nout + n0 + wn * WTN;
+#pragma unroll
+            for (int jq = 0; jq < NB * 4; ++jq)
+                v[jq] = *reinterpret_cast<const f32x4*>(orow + (jq >> 2) * 32 + 8 * (jq & 3) + 4 * g);
+        };
+        load_block(0, cur);
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
+            if (i + 1 < MB) load_block(i + 1 < MB ? i + 1 : 0, nxt);
             const int gm = m0 + wm * WTM + i * 32 + r;
-            if (gm >= M) continue;                                 // both lanes of a row leave together
-            float* orow = (float*)out_ + (size_t)gm * Nout + n0 + wn * WTN;
-            T* arow = (T*)nf.a16 + (size_t)gm * Nout + n0 + wn * WTN;
-            const float* grow = nf.gain + n0 + wn * WTN;
+            const bool live = gm < M;                              // both lanes of a row agree
+            float* orow = (float*)out_ + (size_t)(live ? gm : M - 1) * Nout + n0 + wn * WTN;
+            T* arow = (T*)nf.a16 + (size_t)(live ? gm : M - 1) * Nout + n0 + wn * WTN;
             float ss = 0.f;
 #pragma unroll
-            for (int j = 0; j < NB; ++j)
+            for (int jq = 0; jq < NB * 4; ++jq) {
+                const int c = (jq >> 2) * 32 + 8 * (jq & 3) + 4 * g;
+                f32x4 v = cur[jq];
+                V4 a;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int c = j * 32 + 8 * q + 4 * g;
-                    f32x4* p = reinterpret_cast<f32x4*>(orow + c);
-                    f32x4 v = *p;
-                    const f32x4 gn = *reinterpret_cast<const f32x4*>(grow + c);
-                    V4 a;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        v[t] += acc[j][i][q * 4 + t];
-                        ss += v[t] * v[t];
-                        a[t] = (T)(v[t] * gn[t]);
-                    }
-                    *p = v;
+                for (int t = 0; t < 4; ++t) {
+                    v[t] += acc[jq >> 2][i][(jq & 3) * 4 + t];
+                    ss += v[t] * v[t];
+                    a[t] = (T)(v[t] * gn[jq][t]);
+                }
+                if (live) {
+                    *reinterpret_cast<f32x4*>(orow + c) = v;
                     *reinterpret_cast<V4*>(arow + c) = a;
                 }
+            }
             ss += __shfl_xor(ss, 32, 64);
-            if (g == 0) nf.ss_out[(size_t)gm * n_slots + slot] = ss;
+            if (live && g == 0) nf.ss_out[(size_t)gm * n_slots + slot] = ss;
+#pragma unroll
+            for (int jq = 0; jq < NB * 4; ++jq) cur[jq] = nxt[jq];
         }
     } else if (EPI == EPI_RESIDUAL || EPI == EPI_STORE_F32) {
         // fp32 read-modify-write of the residual stream (or a plain fp32 store) straight from the accumulator layout: per

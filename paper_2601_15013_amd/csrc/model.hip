@@ -137,6 +137,7 @@ int check_config(const radix_model_config& c) {
     if (c.d_int % 32 != 0) return RADIX_ERR_UNSUPPORTED;       // gate/up interleave granularity
     if (c.d % 4 != 0 || c.head_dim % 4 != 0) return RADIX_ERR_UNSUPPORTED;   // 16-byte rows
     if (c.hilo_layers < -1) return RADIX_ERR_BAD_CONFIG;
+    if (c.fold_norms != 0 && c.fold_norms != 1) return RADIX_ERR_BAD_CONFIG;
     if (c.lm_head < 0 || c.lm_head > 2) return RADIX_ERR_BAD_CONFIG;
     if (c.lm_head && c.dtype == RADIX_BF16 && (c.vocab % 128 != 0)) return RADIX_ERR_UNSUPPORTED;
     if (c.hilo_layers > 0 && (c.dtype != RADIX_BF16 || c.d % 256 != 0)) return RADIX_ERR_UNSUPPORTED;
@@ -370,11 +371,12 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         launch_gemm_f32((const float*)A, (const float*)W, M, Nout, K, epi, (float*)o, stream);
         return RADIX_OK;
     };
-    // RMSNorm folded into the GEMMs around it (16-bit operands, d a multiple of 256, layers without (hi, lo) inputs):
+    // RMSNorm folded into the GEMMs around it (config.fold_norms; 16-bit operands, d a multiple of 256, layers without
+    // (hi, lo) inputs):
     // the projection that last updates the residual rows also writes T(x * gain) and the rows' sums of squares, and
     // the projection that consumes the norm scales its rows by rsqrt(mean + eps).  `normed` says that `a` and `ss`
     // already hold that for the norm about to run.
-    const bool can_fold = dt != RADIX_F32 && d % 256 == 0;
+    const bool can_fold = c.fold_norms == 1 && dt != RADIX_F32 && d % 256 == 0;
     const int n_slots = d / 128;
     bool normed = false;
     NormFusion consume = {};

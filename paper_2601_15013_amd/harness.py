@@ -15,11 +15,11 @@ def _to_dev(a: np.ndarray, dtype: torch.dtype, device: str) -> torch.Tensor:
 
 
 def upload_model(weights: synth.SynthWeights, device: str = "cuda", lm_head=None, compute_dtype: Optional[str] = None,
-                 hilo_layers: int = 0, lm_head_mode: int = 0) -> binding.Model:
+                 hilo_layers: int = 0, lm_head_mode: int = 0, fold_norms: int = 0) -> binding.Model:
     """Generate the weights layer by layer, copy them to the GPU and create the library model
     (which keeps its own re-packed copy, so the uploaded tensors are released afterwards).
-    compute_dtype / hilo_layers / lm_head_mode are the library-side settings of radix_model_config
-    (operand type, leading layers with (hi, lo) GEMM inputs, LM head); lm_head: the separate head matrix
+    compute_dtype / hilo_layers / lm_head_mode / fold_norms are the library-side settings of radix_model_config
+    (operand type, leading layers with (hi, lo) GEMM inputs, LM head, RMSNorms folded into the GEMMs); lm_head: the separate head matrix
     for lm_head_mode 2."""
     cfg = weights.cfg
     mt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
@@ -31,7 +31,7 @@ def upload_model(weights: synth.SynthWeights, device: str = "cuda", lm_head=None
         layers.append({k: _to_dev(v, torch.float32 if k.startswith("g") else mt, device) for k, v in lw.items()})
     head = None if lm_head is None else _to_dev(lm_head, mt, device)      # only read when lm_head_mode == 2
     model = binding.radix_model_create(cfg, embed, gf, layers, lm_head=head, compute_dtype=compute_dtype,
-                                       hilo_layers=hilo_layers, lm_head_mode=lm_head_mode)
+                                       hilo_layers=hilo_layers, lm_head_mode=lm_head_mode, fold_norms=fold_norms)
     torch.cuda.synchronize()
     return model
 

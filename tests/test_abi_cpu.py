@@ -77,7 +77,7 @@ def test_model_create_rejects_bad_config(lib):
     assert lib.radix_model_create(None, None, C.byref(out)) == -1
     w = binding.radix_weights(0x1000, 0x1000, None, None)
     good = dict(n_layers=1, d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_int=768, vocab=10, max_pos=16,
-                qk_norm=1, dtype=0, compute_dtype=0, hilo_layers=0, lm_head=0, eps=1e-6, rope_base=1e6)
+                qk_norm=1, dtype=0, compute_dtype=0, hilo_layers=0, fold_norms=0, lm_head=0, eps=1e-6, rope_base=1e6)
 
     def create(**kw):
         c = binding.radix_model_config(**dict(good, **kw))
@@ -93,6 +93,7 @@ def test_model_create_rejects_bad_config(lib):
     assert create(hilo_layers=-2) == -9
     assert create(hilo_layers=-1) == -1          # "none" is fine with fp32 weights (config passes, layers_host NULL)
     assert create(lm_head=3) == -9
+    assert create(fold_norms=2) == -9
     assert create(dtype=1, compute_dtype=2, head_dim=128, n_q_heads=2, n_kv_heads=1, d=256, d_int=512, vocab=1000, lm_head=1) == -3   # 16-bit head: vocab % 128
     assert create(dtype=1, compute_dtype=0, head_dim=128) == -3
     assert create(d_int=100) == -3               # gate/up interleave needs multiples of 32

@@ -21,9 +21,10 @@ TOL_F32 = 1e-4
 TOL_BF16 = 2e-2          # bf16 weights
 
 
-def run_all(weights, batch, pos=None, compute=None, hilo=0, **kw):
-    """compute / hilo: radix_model_config.compute_dtype / hilo_layers (None / 0 = what a caller gets by default)."""
-    model = harness.upload_model(weights, compute_dtype=compute, hilo_layers=hilo)
+def run_all(weights, batch, pos=None, compute=None, hilo=0, fold=0, **kw):
+    """compute / hilo / fold: radix_model_config.compute_dtype / hilo_layers / fold_norms (None / 0 / 0 = what a caller
+    gets by default)."""
+    model = harness.upload_model(weights, compute_dtype=compute, hilo_layers=hilo, fold_norms=fold)
     try:
         run = harness.Runner(model, batch.N, batch.B)
         tok, cu = harness.upload_batch(batch)
@@ -151,6 +152,31 @@ def test_16bit_qkv_row_of_640_takes_the_unfused_qknorm_rope_kernel(compute, qk_n
         print(f"row 640, {compute} operands, qk_norm={qk_norm}, fused attention={fused}: err {e:.3e}")
         assert e <= (TOL_BF16 if compute == "f16" else 5e-2)       # bf16 operands: sanity bound only
         assert np.array_equal(y, y_nd)
+
+
+@pytest.mark.parametrize("hilo", [-1, 1])
+def test_rmsnorms_folded_into_the_gemms(hilo):
+    # fold_norms = 1: O / down epilogues write the next norm's operand and sums of squares, QKV / gate-up scale their
+    # rows; same error as the norm kernels, row-invariant, both attention modes, with and without a leading (hi, lo)
+    # layer (whose norms stay kernels of their own), ragged M over several tiles
+    w = synth.SynthWeights(SMALL_BF16, 31)
+    b = synth.multilevel_batch(6, 12, 150, 3, 40, 1, 300, SMALL_BF16.vocab)
+    ref = U.oracle_rows(w, b)
+    base = U.rms_err(run_all(w, b, hilo=hilo)[0], ref)
+    for fused in (False, True):
+        y, y_nd, _ = run_all(w, b, hilo=hilo, fold=1, fused_attention=fused)
+        e = U.rms_err(y, ref)
+        print(f"folded norms, hilo={hilo}, fused attention={fused}: rms err {e:.3e} (norm kernels: {base:.3e})")
+        assert U.rel_err(y, ref) <= TOL_BF16 and e <= 1.3 * base
+        assert np.array_equal(y, y_nd)
+    # a wide model: the 256x256 and 128x256 tiles, 4 column tiles per row
+    cfg = synth.ModelConfig("bf16w", 2, 1024, 8, 2, 128, 1536, 3000, "bf16", max_pos=1024)
+    w = synth.SynthWeights(cfg, 35)
+    b = synth.shared_prefix_batch(8, 40, 100, 150, 260, cfg.vocab)
+    y, y_nd, n_c = run_all(w, b, hilo=hilo, fold=1)
+    seqs = [0, 7, 39]
+    assert U.rel_err(y[U.rows_of(b, seqs)], U.oracle_rows(w, b, sequences=seqs)) <= TOL_BF16
+    assert np.array_equal(y, y_nd)
 
 
 def test_bf16_wide_model_uses_large_gemm_tiles():
