@@ -309,8 +309,8 @@ def _time_ms(torch, fn, iters, warmup):
 
 def sweep_table_bench(args, torch, np, binding, harness, synth):
     """Every (prefix, suffix) row of the paper's sweep for one model shape, one model upload: forward time without
-    deduplication, with it (the library's default attention mode) and with Algorithm 1's three-kernel attention (gated
-    by the library's cost model, and with deduplication forced).
+    deduplication, with the library's defaults (fused attention kernel, gated by the library's cost model; and with
+    deduplication forced) and with Algorithm 1's three-kernel attention (gated, and forced).
     Timings exclude the index build, as the paper's do."""
     model_cfg = {"0.6B": synth.QWEN3_0_6B, "4B": synth.QWEN3_4B, "8B": synth.QWEN3_8B}[args.sweep_model]
     weights = synth.SynthWeights(model_cfg, SWEEP_SEED)
@@ -330,15 +330,17 @@ def sweep_table_bench(args, torch, np, binding, harness, synth):
         t_nd = _time_ms(torch, lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, batch.max_seqlen,
                                                                               run.ws, out=o), args.steps, args.warmup)
         t_def = _time_ms(torch, lambda: fwd(None), args.steps, args.warmup)
+        t_forced = _time_ms(torch, lambda: fwd(None, True), args.steps, args.warmup)
         t_3k = _time_ms(torch, lambda: fwd(False), args.steps, args.warmup)           # gated by the library's cost model
         t_3k_forced = _time_ms(torch, lambda: fwd(False, True), args.steps, args.warmup)
         assert run.status() == 0
         rows.append({"prefix": prefix, "suffix": suffix, "N": batch.N, "N_compact": n_c, "gamma": n_c / batch.N,
                      "nodedup_ms": t_nd, "dedup_ms": t_def, "speedup": t_nd / t_def,
+                     "forced_ms": t_forced, "forced_speedup": t_nd / t_forced,
                      "three_kernel_ms": t_3k, "three_kernel_speedup": t_nd / t_3k,
                      "three_kernel_forced_ms": t_3k_forced, "three_kernel_forced_speedup": t_nd / t_3k_forced})
-        print(f"{args.sweep_model} {prefix}/{suffix}: N {batch.N} N' {n_c} no-dedup {t_nd:.1f} ms, dedup {t_def:.1f} ms "
-              f"({t_nd / t_def:.2f}x), three-kernel attention {t_3k:.1f} ms ({t_nd / t_3k:.2f}x; deduplication forced: "
+        print(f"{args.sweep_model} {prefix}/{suffix}: N {batch.N} N' {n_c} no-dedup {t_nd:.1f} ms, default {t_def:.1f} ms "
+              f"({t_nd / t_def:.2f}x; deduplication forced: {t_forced:.1f} ms, {t_nd / t_forced:.2f}x), three-kernel attention {t_3k:.1f} ms ({t_nd / t_3k:.2f}x; deduplication forced: "
               f"{t_3k_forced:.1f} ms, {t_nd / t_3k_forced:.2f}x)", file=sys.stderr, flush=True)
     head = next(r for r in rows if (r["prefix"], r["suffix"]) == (2048, 256))
     model.close()

@@ -126,13 +126,12 @@ enum { RADIX_ATTN_AUTO = 0, RADIX_ATTN_THREE_KERNELS = 1, RADIX_ATTN_FUSED = 2 }
  * the radix_mlp_threshold setting of the end-to-end experiments). */
 typedef struct radix_fwd_opts {
     float threshold;      /* deduplicate iff n_compact < threshold * N; 1.0 = whenever anything is shared, 0.0 = never
-                           * (the paper's radix_mlp_threshold).  Negative (RADIX_THRESHOLD_AUTO): the library decides.
-                           * With the fused attention kernel deduplication costs nothing when little is shared, so
-                           * that is 1.0.  With the three-kernel attention it pays for a scatter of (N' + N) q|k|v
-                           * rows per layer with the position-wise work of the N - N' rows it saves:
-                           * deduplicate iff (N - N') * F / 1.1e15 > (N' + N) * q|k|v row bytes / 5e12, F the
-                           * projection + MLP flops of one row and layer (rates: what the GEMMs and the row copy
-                           * reach on an MI355X); about N'/N < 0.89 for the 0.6B shape, < 0.99 for the 8B shape. */
+                           * (the paper's radix_mlp_threshold).  Negative (RADIX_THRESHOLD_AUTO): the library decides, per
+                           * layer: the position-wise work saved, (N - N') * F / 1.1e15 s (F = projection + MLP flops of
+                           * one row), against what deduplication adds - with the fused attention kernel about 15 % of
+                           * the attention time, 0.15 * 2 * dq * N * (N / B) / 5e14 s; with the three-kernel attention the
+                           * scatter of (N' + N) q|k|v rows at 5e12 bytes/s.  (Rates: what the kernels reach on an
+                           * MI355X.)  E.g. the 0.6B shape with 1024-token sequences deduplicates below N'/N = 0.93. */
     int32_t force_dedup;  /* 1: always take the deduplicated path, whatever the threshold says */
     int32_t attention_mode;  /* How scatter -> attention -> gather (Algorithm 1) is executed on the deduplicated path.
                               *  RADIX_ATTN_AUTO (0): the fused kernel where it applies (16-bit operand configurations,

@@ -124,7 +124,9 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
         const long long wi = (long long)((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
         if ((int)blockIdx.x / 8 >= per_xcd || wi >= total) return;
         hgroup = (int)(wi / n_items);
-        const int item = (int)(wi % n_items);
+        // last item first: the packed items, then every sequence's blocks from its last (most keys) to its first,
+        // so that the workgroups still running when the grid drains are the light ones
+        const int item = n_items - 1 - (int)(wi % n_items);
         const int ts = plan[pl.t_shared + item];
         int last_tile = -1;
 #pragma unroll
@@ -410,8 +412,14 @@ static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N
     int n_qtiles = 0, n_pairs = 0;
     long long n_blocks;
     if (fused) {
-        // at most max_items items per head group; workgroups past the real count (known on the device) leave at once
-        n_blocks = ((long long)pl.max_items * (n_q_heads / hpb) + 7) / 8 * 8;
+        // The item count is known on the device only.  Its bound: every sequence cuts its R_s representative rows
+        // (sum R_s = n_compact) into ceil(R_s / 32) blocks, `slots` blocks make an item, the packed items round
+        // up once.  Workgroups past the real count leave at once (they still cost a launch each, hence the
+        // tight bound).
+        const int slots = 4 / hpb;
+        long long items = ((long long)n_compact / 32 + B + slots - 1) / slots + 1;
+        if (items > pl.max_items) items = pl.max_items;
+        n_blocks = (items * (n_q_heads / hpb) + 7) / 8 * 8;
     } else {
         n_qtiles = ceil_div(max_seqlen, 128 / hpb);
         n_pairs = (n_q_heads / hpb) * B;

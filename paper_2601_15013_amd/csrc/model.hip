@@ -530,16 +530,25 @@ extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* to
         dedup = true;
     } else if (threshold >= 0.f) {
         dedup = (double)n_compact < (double)threshold * (double)N;
-    } else if (fused) {
-        dedup = n_compact < N;                  // nothing to lose: no [N, .] copies, no attention on duplicate rows
     } else {
-        // three-kernel attention: the scatter's bytes against the position-wise flops of the rows saved
+        // automatic: the position-wise work of the N - N' rows saved against what deduplication adds per layer
         const radix_model_config& c = model->cfg;
         const double dq = (double)c.n_q_heads * c.head_dim, dkv = (double)c.n_kv_heads * c.head_dim;
         const double flops_row = 2.0 * c.d * (dq + 2 * dkv) + 2.0 * dq * c.d + 6.0 * (double)c.d * c.d_int;
-        const double row_bytes = (dq + 2 * dkv) * (double)esize(c.compute_dtype);
-        const double gemm_rate = c.compute_dtype == RADIX_F32 ? 2.0e13 : 1.1e15, copy_rate = 5.0e12;
-        dedup = ((double)N - n_compact) * flops_row / gemm_rate > ((double)N + n_compact) * row_bytes / copy_rate;
+        const double gemm_rate = c.compute_dtype == RADIX_F32 ? 2.0e13 : 1.1e15;
+        const double saved = ((double)N - n_compact) * flops_row / gemm_rate;
+        double added;
+        if (fused) {
+            // the fused kernel starts every workgroup with two more dependent loads (work list, index map) and
+            // cuts query blocks where the representatives start, not at multiples of the key tile: about 15 % on
+            // top of the attention time when nothing is shared
+            const double attn_flops = 2.0 * dq * (double)N * ((double)N / (B > 0 ? B : 1));
+            added = 0.15 * attn_flops / 5.0e14;
+        } else {
+            // three-kernel attention: the scatter of (N' + N) q|k|v rows
+            added = ((double)N + n_compact) * (dq + 2 * dkv) * (double)esize(c.compute_dtype) / 5.0e12;
+        }
+        dedup = n_compact < N && saved > added;
     }
     if (opts && opts->pad_compact_to < 0) return RADIX_ERR_BAD_CONFIG;
     const int pad_to = opts ? opts->pad_compact_to : 0;

@@ -24,6 +24,7 @@ TOL_BF16 = 2e-2          # bf16 weights
 def run_all(weights, batch, pos=None, compute=None, hilo=0, fold=0, **kw):
     """compute / hilo / fold: radix_model_config.compute_dtype / hilo_layers / fold_norms (None / 0 / 0 = what a caller
     gets by default)."""
+    kw.setdefault("threshold", 1.0)         # deduplicate whenever anything is shared: the tests choose the path, not the gate
     model = harness.upload_model(weights, compute_dtype=compute, hilo_layers=hilo, fold_norms=fold)
     try:
         run = harness.Runner(model, batch.N, batch.B)
@@ -213,6 +214,33 @@ def test_threshold_gating_and_forced_dedup():
     y_forced = run.forward(tok, cu, b.max_seqlen, maps, threshold=0.0, force_dedup=True).cpu()
     y_nd = run.forward_nodedup(tok, cu, b.max_seqlen).cpu()
     assert torch.equal(y_off, y_nd) and torch.equal(y_on, y_nd) and torch.equal(y_forced, y_nd)
+    model.close()
+
+
+def test_automatic_gate_follows_its_cost_model():
+    # RADIX_THRESHOLD_AUTO with the three-kernel attention: deduplicate iff the position-wise work saved outweighs the
+    # scatter.  Which path ran shows in the benchmark hooks: the scatter is launched once per layer, or not at all.
+    w = synth.SynthWeights(SMALL_BF16, 33)
+    model = harness.upload_model(w)
+    shared = synth.shared_prefix_batch(4, 16, 300, 20, 40, 2000)          # N'/N = 0.15: worth it
+    barely = synth.shared_prefix_batch(5, 16, 1, 300, 340, 2000)          # one shared token per sequence: not worth it
+    for b, want in ((shared, SMALL_BF16.n_layers), (barely, 0)):
+        run = harness.Runner(model, b.N, b.B)
+        tok, cu = harness.upload_batch(b)
+        maps = run.build_index(tok, cu)
+        assert maps[3] == b.expected_n_compact < b.N
+        binding.radix_timing_enable(["scatter"])
+        y = run.forward(tok, cu, b.max_seqlen, maps, fused_attention=False).cpu()
+        launches = binding.radix_timing_collect()["scatter"][1]
+        binding.radix_timing_enable([])
+        assert launches == want, (b.name, launches)
+        assert torch.equal(y, run.forward_nodedup(tok, cu, b.max_seqlen).cpu())
+        # an explicit threshold overrides the model either way
+        binding.radix_timing_enable(["scatter"])
+        run.forward(tok, cu, b.max_seqlen, maps, fused_attention=False, threshold=1.0)
+        run.forward(tok, cu, b.max_seqlen, maps, fused_attention=False, threshold=0.0)
+        assert binding.radix_timing_collect()["scatter"][1] == SMALL_BF16.n_layers
+        binding.radix_timing_enable([])
     model.close()
 
 
