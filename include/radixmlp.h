@@ -65,13 +65,15 @@ typedef struct radix_model_config {
                               RADIX_F16 converts the weights once at create time (exact for every bf16
                               value of magnitude >= 2^-17) and carries 11-bit instead of 8-bit
                               significands through the activations; activations must stay below 65504. */
-    int32_t hilo_layers; /* Number of leading layers that carry every GEMM input (both RMSNorm outputs, the attention
-                            output, the SwiGLU output) as a 16-bit (hi, lo) pair and multiply over the doubled K against
-                            the weights read twice: about twice the significand at those rounding points for twice the
-                            GEMM work in those layers (bf16 weights only, d a multiple of 256).  Rounding errors of the
-                            first layers dominate the final error of deep models whose projections do not attenuate
-                            (their outputs are the whole residual stream at that depth).
-                            0: decided from the weights at create time: RADIX_HILO_AUTO_LAYERS layers when
+    int32_t hilo_layers; /* Number of leading layers that carry every value they round to the operand type as a 16-bit
+                            (hi, lo) pair: both RMSNorm outputs, the attention output and the SwiGLU output (their GEMMs
+                            run over the doubled K against the weights read twice), and q, k, v (attention multiplies
+                            K_hi Q_hi + K_hi Q_lo + K_lo Q_hi and adds V_hi and V_lo products).  About twice the
+                            significand at those points for twice the GEMM work in those layers (bf16 weights only, d a
+                            multiple of 256; q, k, v only when the fused q|k|v row is a multiple of 256 wide).  Rounding
+                            errors of the first layer dominate the final error of deep models whose projections do not
+                            attenuate (its outputs are the whole residual stream at that depth).
+                            0: decided from the weights at create time: RADIX_HILO_AUTO_LAYERS layer(s) when
                                rms(Wq of layer 0) * sqrt(d) >= RADIX_HILO_AUTO_GAIN, else none;
                             k > 0: the first min(k, n_layers) layers;  -1: none. */
     int32_t fold_norms;  /* 1: fold every RMSNorm that sits between two 16-bit GEMMs into them (bf16 weights, d a multiple of
@@ -92,7 +94,7 @@ typedef struct radix_model_config {
 
 /* The automatic setting of radix_model_config.hilo_layers. */
 #define RADIX_HILO_AUTO_GAIN 0.85
-#define RADIX_HILO_AUTO_LAYERS 2
+#define RADIX_HILO_AUTO_LAYERS 1
 
 /* Per-layer weights.  Matrices are [out, in] row-major as in y = W h (paper Eq. 5), stored
  * in config.dtype.  RMSNorm gains are always fp32.  All pointers are device pointers. */

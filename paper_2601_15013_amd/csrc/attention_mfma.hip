@@ -59,8 +59,8 @@ __device__ __forceinline__ uint32_t att_lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int DT, int HPB, bool FUSED>
-__global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
+template <int DT, int HPB, bool FUSED, bool SPLIT>
+__global__ __launch_bounds__(ATT_THREADS, SPLIT ? 1 : 2) void attention_mfma_kernel(const typename Op<DT>::T* __restrict__ qkv,
                                                                         const int32_t* __restrict__ cu, int N,
                                                                         int n_q_heads, int n_kv_heads, int n_qtiles,
                                                                         int n_pairs,
@@ -74,8 +74,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     typedef typename Op<DT>::V4 V4;
     // [stage][key][16 chunks of 8 hd].  K: chunk ^= key & 15 (a fragment read walks 16 keys of one
     // chunk column).  V: chunk ^= (key & 3) << 2 (a transpose read walks 4 keys of one 64-byte column block).
-    __shared__ uint4 Ks[2][TILE_SLOTS];
-    __shared__ uint4 Vs[2][TILE_SLOTS];
+    // SPLIT: q, k and v come as 16-bit (hi, lo) pairs (a row of the input is [q | k | v] hi, then [q | k | v] lo):
+    // the tiles of both parts are staged, scores are K_hi Q_hi + K_hi Q_lo + K_lo Q_hi (the lo * lo term is below fp32
+    // resolution) and the second product adds V_hi^T P^T and V_lo^T P^T.
+    constexpr int NP = SPLIT ? 2 : 1;
+    __shared__ uint4 Ks[2][NP][TILE_SLOTS];
+    __shared__ uint4 Vs[2][NP][TILE_SLOTS];
 
     constexpr int BQ = 128 / HPB;                       // query rows per workgroup
     constexpr int WPH = 4 / HPB;                        // wavefronts per query head = 32-row slots per workgroup
@@ -168,7 +172,8 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     const int h = hgroup * HPB + wave / WPH;            // query head of this wavefront
     const int kvh = (hgroup * HPB) / group;             // one KV head per workgroup: HPB divides group
     const int dq = n_q_heads * HD, dkv = n_kv_heads * HD;
-    const size_t row = (size_t)dq + 2 * (size_t)dkv;
+    const size_t row = ((size_t)dq + 2 * (size_t)dkv) * NP;     // elements of an input row (both parts)
+    const size_t lo_off = (size_t)dq + 2 * (size_t)dkv;         // SPLIT: where the lo part of a row starts
     const uint32_t row_bytes = (uint32_t)(row * sizeof(T));
     // K/V base: the compact buffer (FUSED: rows come from the map) or, full layout, the rows of the one sequence
     const char* kbase = (const char*)(qkv + (FUSED ? (size_t)0 : (size_t)slot_start[0] * row) + dq + (size_t)kvh * HD);
@@ -223,8 +228,13 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
             int kr = kv0 + r;
             kr = kr < tl ? kr : tl - 1;
             const uint32_t rb = (uint32_t)(FUSED ? krow[j] : kr) * row_bytes;
-            att_dma16(kbase, rb + 16u * (uint32_t)(lpc ^ (r & 15)), att_lds_addr(&Ks[stage][(16 * wave + 4 * j) * 16]));
-            att_dma16(vbase, rb + 16u * (uint32_t)(lpc ^ ((r & 3) << 2)), att_lds_addr(&Vs[stage][(16 * wave + 4 * j) * 16]));
+#pragma unroll
+            for (int p = 0; p < NP; ++p) {
+                att_dma16(kbase + p * lo_off * sizeof(T), rb + 16u * (uint32_t)(lpc ^ (r & 15)),
+                          att_lds_addr(&Ks[stage][p][(16 * wave + 4 * j) * 16]));
+                att_dma16(vbase + p * lo_off * sizeof(T), rb + 16u * (uint32_t)(lpc ^ ((r & 3) << 2)),
+                          att_lds_addr(&Vs[stage][p][(16 * wave + 4 * j) * 16]));
+            }
         }
     };
     const int wave_qmin = q0w, wave_qmax = q0w + 31;
@@ -235,14 +245,17 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
     // ---- Q fragment (B operand of S^T = K Q^T): lane (n, g) holds Q[query n][16 ks + 8 g .. +8]
     const int qi = q0w + n;                             // query offset inside the sequence
     const int qi_c = qi < len ? qi : (len > 0 ? len - 1 : 0);
-    V8 qf[8];
+    V8 qf[NP][8];
     {
         const size_t qrow = FUSED ? (len > 0 ? (size_t)compact_row(start, qi_c) : (size_t)0) : (size_t)(start + qi_c);
-        const uint4* qp = (const uint4*)(qkv + qrow * row + (size_t)h * HD);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            uint4 v = qp[ks * 2 + g];
-            qf[ks] = *reinterpret_cast<V8*>(&v);
+        for (int p = 0; p < NP; ++p) {
+            const uint4* qp = (const uint4*)(qkv + qrow * row + p * lo_off + (size_t)h * HD);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                uint4 v = qp[ks * 2 + g];
+                qf[p][ks] = *reinterpret_cast<V8*>(&v);
+            }
         }
     }
 
@@ -286,29 +299,33 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
 #pragma unroll
             for (int e = 0; e < 16; ++e) s[kb][e] = 0.f;
         {
+            // terms: K_hi Q_hi [, K_hi Q_lo, K_lo Q_hi]; MFMA u: term u >> 4, key block u & 1, k-step (u & 15) >> 1
+            constexpr int NS_ = (SPLIT ? 3 : 1) * 16;
             uint4 kf[16];
             auto read_k = [&](int u) {
-                const int key = (u & 1) * 32 + n;
-                kf[u] = Ks[st][key * 16 + (((u >> 1) * 2 + g) ^ (key & 15))];
+                const int uu = u & 15, key = (uu & 1) * 32 + n;
+                kf[uu] = Ks[st][(u >> 4) == 2 ? NP - 1 : 0][key * 16 + (((uu >> 1) * 2 + g) ^ (key & 15))];
             };
 #pragma unroll
             for (int u = 0; u < 4; ++u) read_k(u);
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                if (u + 4 < 16) read_k(u + 4 < 16 ? u + 4 : 0);
-                s[u & 1] = Op<DT>::mfma(*reinterpret_cast<V8*>(&kf[u]), qf[u >> 1], s[u & 1]);
+            for (int u = 0; u < NS_; ++u) {
+                if (u + 4 < NS_) read_k(u + 4 < NS_ ? u + 4 : 0);
+                s[u & 1] = Op<DT>::mfma(*reinterpret_cast<V8*>(&kf[u & 15]), qf[(u >> 4) == 1 ? NP - 1 : 0][(u & 15) >> 1], s[u & 1]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         // V^T fragments of the second product, MFMA u: k-step u >> 2 (16 keys), hd block u & 3.  The first
         // four are requested now and arrive during the softmax.
-        const char* vt = (const char*)&Vs[st][0];
+        // (SPLIT: u >> 4 picks the part of V; the ring of 16 fragment registers is indexed by u & 15)
+        constexpr int NV_ = NP * 16;
         s16x4 vlo[16], vhi[16];
         auto read_v = [&](int u) {
-            const int kk = u >> 2, b = u & 3;
+            const char* vt = (const char*)&Vs[st][u >> 4][0];
+            const int kk = (u & 15) >> 2, b = u & 3;
             const uint32_t off = tr_key0 + (uint32_t)kk * 4096u + (uint32_t)(((4 * b + tr_chunk0) ^ (tr_e << 2)) << 4);
-            vlo[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vt + off));
-            vhi[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vt + off + 2048u));
+            vlo[u & 15] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vt + off));
+            vhi[u & 15] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vt + off + 2048u));
         };
 #pragma unroll
         for (int u = 0; u < 4; ++u) read_v(u);
@@ -360,12 +377,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
         // which is the order the P^T registers of k-step kk are in.
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            if (u + 4 < 16) read_v(u + 4 < 16 ? u + 4 : 0);
+        for (int u = 0; u < NV_; ++u) {
+            if (u + 4 < NV_) read_v(u + 4 < NV_ ? u + 4 : 0);
             union { struct { s16x4 lo, hi; } p; V8 v; } cvt;
-            cvt.p.lo = vlo[u];
-            cvt.p.hi = vhi[u];
-            o[u & 3] = Op<DT>::mfma(cvt.v, pf[u >> 2], o[u & 3]);
+            cvt.p.lo = vlo[u & 15];
+            cvt.p.hi = vhi[u & 15];
+            o[u & 3] = Op<DT>::mfma(cvt.v, pf[(u & 15) >> 2], o[u & 3]);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -398,7 +415,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_mfma_kernel(const ty
 
 static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
                                 int n_kv_heads, int hd, void* out, int op_dtype, const int32_t* iscat,
-                                const int32_t* plan, int n_compact, int split_out, hipStream_t stream) {
+                                const int32_t* plan, int n_compact, int split_out, int split_in, hipStream_t stream) {
     const bool fused = iscat != nullptr;
     if (N <= 0 || B <= 0) return RADIX_OK;
     if (hd != HD) return RADIX_ERR_UNSUPPORTED;
@@ -428,36 +445,43 @@ static int launch_attention_any(const void* qkv, const int32_t* cu, int B, int N
     if (n_blocks > 0x7FFFFFFFLL) return RADIX_ERR_UNSUPPORTED;
     // per-lane 32-bit byte offsets: inside one sequence's K/V rows, or (fused) inside the compact buffer
     const long long span_rows = fused ? (long long)n_compact : (long long)max_seqlen;
-    if (span_rows * (n_q_heads + 2 * n_kv_heads) * HD * 2 >= (1LL << 32)) return RADIX_ERR_UNSUPPORTED;
+    if (span_rows * (n_q_heads + 2 * n_kv_heads) * HD * 2 * (split_in ? 2 : 1) >= (1LL << 32)) return RADIX_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)n_blocks), block(ATT_THREADS);
-#define RADIX_ATT(DT, HPB, F)                                                                                      \
-    hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB, F>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu, N,  \
-                       n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, plan, pl, n_compact,      \
+#define RADIX_ATT(DT, HPB, F, S)                                                                                   \
+    hipLaunchKernelGGL((attention_mfma_kernel<DT, HPB, F, S>), grid, block, 0, stream, (const Op<DT>::T*)qkv, cu,  \
+                       N, n_q_heads, n_kv_heads, n_qtiles, n_pairs, (Op<DT>::T*)out, iscat, plan, pl, n_compact,   \
                        split_out)
-#define RADIX_ATT_H(DT, F)                                                                                         \
+#define RADIX_ATT_H(DT, F, S)                                                                                      \
     do {                                                                                                           \
-        if (hpb == 4) RADIX_ATT(DT, 4, F); else if (hpb == 2) RADIX_ATT(DT, 2, F); else RADIX_ATT(DT, 1, F);       \
+        if (hpb == 4) RADIX_ATT(DT, 4, F, S); else if (hpb == 2) RADIX_ATT(DT, 2, F, S); else RADIX_ATT(DT, 1, F, S); \
+    } while (0)
+#define RADIX_ATT_S(DT, F)                                                                                         \
+    do {                                                                                                           \
+        if (split_in) RADIX_ATT_H(DT, F, true); else RADIX_ATT_H(DT, F, false);                                    \
     } while (0)
     if (op_dtype == RADIX_BF16) {
-        if (fused) RADIX_ATT_H(RADIX_BF16, true); else RADIX_ATT_H(RADIX_BF16, false);
+        if (fused) RADIX_ATT_S(RADIX_BF16, true); else RADIX_ATT_S(RADIX_BF16, false);
     } else {
-        if (fused) RADIX_ATT_H(RADIX_F16, true); else RADIX_ATT_H(RADIX_F16, false);
+        if (fused) RADIX_ATT_S(RADIX_F16, true); else RADIX_ATT_S(RADIX_F16, false);
     }
+#undef RADIX_ATT_S
 #undef RADIX_ATT_H
 #undef RADIX_ATT
     return RADIX_OK;
 }
 
 int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out) {
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out,
+                          int split_in) {
     return launch_attention_any(qkv, cu, B, N, max_seqlen, n_q_heads, n_kv_heads, hd, out, op_dtype, nullptr, nullptr,
-                                0, split_out, stream);
+                                0, split_out, split_in, stream);
 }
 
 int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
                                 const int32_t* plan, int B, int N, int n_compact, int n_q_heads,
-                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream, int split_out) {
+                                int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream, int split_out,
+                                int split_in) {
     if (I_scatter == nullptr) return RADIX_ERR_BAD_SIZE;
     return launch_attention_any(qkv_c, cu, B, N, 0, n_q_heads, n_kv_heads, hd, out_c, op_dtype, I_scatter,
-                                plan, n_compact, split_out, stream);
+                                plan, n_compact, split_out, split_in, stream);
 }

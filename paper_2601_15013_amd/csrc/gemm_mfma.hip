@@ -54,8 +54,15 @@ template <int N> __device__ __forceinline__ void wait_vmcnt_and_lds() {
 // [lds_base + 16 L, +16).  lds_base must be wave-uniform.  (s_nop: M0 write -> LDS-DMA hazard.)
 // The global address is (uniform 64-bit base) + (per-lane 32-bit byte offset).
 __device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_base) {
+    // the base is wave-uniform by construction; readfirstlane states that where the compiler has parked it in
+    // vector registers (it must reach the instruction in a scalar register pair)
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    // (the builtin returns a signed int: through uint32_t, or a low half with its top bit set would sign-extend
+    // over the high half)
+    const uint64_t bs = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(b >> 32)) << 32) |
+                        (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 ::"v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+                 ::"v"(lane_off), "s"(bs), "s"(lds_base) : "memory");
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
@@ -84,9 +91,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     constexpr int LOADS = A_LOADS + B_LOADS;
     constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
     constexpr bool SWIGLU = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_SPLIT;
-    constexpr int PARTS = EPI == EPI_SWIGLU_SPLIT ? 2 : 1;     // (hi, lo) halves of the SwiGLU output row
+    constexpr bool ROPE = EPI == EPI_QKV_ROPE || EPI == EPI_QKV_ROPE_SPLIT;
+    constexpr int PARTS = (EPI == EPI_SWIGLU_SPLIT || EPI == EPI_QKV_ROPE_SPLIT) ? 2 : 1;     // (hi, lo) halves of the output row
     static_assert(!SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
-    static_assert(EPI != EPI_QKV_ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
+    static_assert(!ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
     static_assert(EPI != EPI_RESIDUAL_NORM || WTN == 128, "sum-of-squares slots are 128 columns = one wavefront");
     static_assert(LOADS * 2 + (BM / 64) * 2 < 64, "vmcnt range");
 
@@ -164,7 +172,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     // EPI_QKV_ROPE: position ids of this lane's rows, fetched before the main loop so that the RoPE
     // table rows can be addressed without a dependent load when the epilogue starts
     int rope_pos[MB];
-    if (EPI == EPI_QKV_ROPE) {
+    if (ROPE) {
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
             int gm = m0 + wm * WTM + i * 32 + r;
@@ -553,12 +561,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
         constexpr int CHUNKS = OUT_COLS / 8;                    // 16-byte chunks per output row
         constexpr int ROWS_PER_INST = 64 / CHUNKS;
         const int orow = lane / CHUNKS, ochunk = lane % CHUNKS;
-        const int ldo = SWIGLU ? (Nout >> 1) * PARTS : Nout;
+        const int out_w = SWIGLU ? (Nout >> 1) : Nout;          // logical output width; a (hi, lo) row is twice that
+        const int ldo = out_w * PARTS;
         const int ncol0 = SWIGLU ? ((n0 + wn * WTN) >> 1) : (n0 + wn * WTN);
-        // EPI_QKV_ROPE: which head this wavefront's columns are, and whether it is rotated (q, k) or not (v)
+        // Q/K-norm + RoPE: which head this wavefront's columns are, and whether it is rotated (q, k) or not (v)
         const int head = (n0 + wn * WTN) >> 7;
-        const bool rope_head = EPI == EPI_QKV_ROPE && head < qe.n_q_heads + qe.n_kv_heads;
-        const float* rope_gain = (EPI == EPI_QKV_ROPE && head >= qe.n_q_heads) ? qe.gk : qe.gq;
+        const bool rope_head = ROPE && head < qe.n_q_heads + qe.n_kv_heads;
+        const float* rope_gain = (ROPE && head >= qe.n_q_heads) ? qe.gk : qe.gq;
 #pragma unroll
         for (int ip = 0; ip < MB; ip += 2) {
 #pragma unroll
@@ -582,7 +591,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                             }
                             *reinterpret_cast<V4*>(rowp + ((j >> 1) * 32 + 8 * q + 4 * g) * 2) = v;
                         }
-                } else if (EPI == EPI_QKV_ROPE && rope_head) {
+                } else if (ROPE && rope_head) {
                     // This wavefront's 128 columns are exactly one q or k head of the fused q|k|v row and
                     // a lane owns a row: the per-head RMSNorm is an in-lane sum of 64 squares plus one
                     // exchange with lane ^ 32, and the rotary partner of column c < 64 (block j) is
@@ -618,8 +627,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                             for (int t = 0; t < 4; ++t) {
                                 const float xa = RADIX_ACC(j, i, q * 4 + t) * rs * ga[t];
                                 const float xb = RADIX_ACC(j + 2, i, q * 4 + t) * rs * gb[t];
-                                va[t] = (T)(xa * cs[t] - xb * sn[t]);
-                                vb[t] = (T)(xb * cs[t] + xa * sn[t]);
+                                const float ya = xa * cs[t] - xb * sn[t], yb = xb * cs[t] + xa * sn[t];
+                                const T ha = (T)ya, hb = (T)yb;
+                                va[t] = part == 0 ? ha : (T)(ya - (float)ha);
+                                vb[t] = part == 0 ? hb : (T)(yb - (float)hb);
                             }
                             *reinterpret_cast<V4*>(rowp + c * 2) = va;
                             *reinterpret_cast<V4*>(rowp + (c + 64) * 2) = vb;
@@ -632,7 +643,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                         for (int q = 0; q < 4; ++q) {
                             V4 v;
 #pragma unroll
-                            for (int t = 0; t < 4; ++t) v[t] = (T)RADIX_ACC(j, ip + il, q * 4 + t);
+                            for (int t = 0; t < 4; ++t) {
+                                const float y = RADIX_ACC(j, ip + il, q * 4 + t);
+                                const T hi = (T)y;
+                                v[t] = part == 0 ? hi : (T)(y - (float)hi);
+                            }
                             *reinterpret_cast<V4*>(rowp + (j * 32 + 8 * q + 4 * g) * 2) = v;
                         }
                 }
@@ -643,7 +658,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
                 const int gm = m0 + wm * WTM + ip * 32 + row;
                 const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * PITCH + ochunk * 16);
                 if (gm < M)
-                    *reinterpret_cast<uint4*>((T*)out_ + (size_t)gm * ldo + part * (Nout >> 1) + ncol0 + ochunk * 8) = v;
+                    *reinterpret_cast<uint4*>((T*)out_ + (size_t)gm * ldo + part * out_w + ncol0 + ochunk * 8) = v;
             }
           }
         }
@@ -677,6 +692,9 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     else if (epilogue == EPI_QKV_ROPE) {
         if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_QKV_ROPE);
         else return RADIX_ERR_UNSUPPORTED;
+    } else if (epilogue == EPI_QKV_ROPE_SPLIT) {
+        if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_QKV_ROPE_SPLIT);
+        else return RADIX_ERR_UNSUPPORTED;
     } else return RADIX_ERR_UNSUPPORTED;
 #undef RADIX_LAUNCH
     return RADIX_OK;
@@ -703,7 +721,8 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int
         double best = 0.0;
         for (const Shape& sh : shapes) {
             if (Nout % sh.bn != 0) continue;
-            if ((epilogue == EPI_QKV_ROPE || epilogue == EPI_RESIDUAL_NORM) && sh.bn != 256) continue;   // need 128-wide wavefront blocks
+            if ((epilogue == EPI_QKV_ROPE || epilogue == EPI_QKV_ROPE_SPLIT || epilogue == EPI_RESIDUAL_NORM) && sh.bn != 256)
+                continue;                                            // need 128-wide wavefront blocks
             const double tiles = (double)ceil_div(M, sh.bm) * (Nout / sh.bn);
             double rounds = tiles / n_cu;
             if (rounds < 8.0) rounds = (double)(long long)(rounds + 0.999999);   // few rounds: the last one counts whole
@@ -728,7 +747,7 @@ int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int e
     if (w_k != K && (2 * w_k != K || w_k % (2 * BK) != 0)) return RADIX_ERR_UNSUPPORTED;
     if ((((uintptr_t)A | (uintptr_t)W | (uintptr_t)out) & 15) != 0) return RADIX_ERR_MISALIGNED;
     QkvEpilogue qe = {};
-    if (epilogue == EPI_QKV_ROPE) {
+    if (epilogue == EPI_QKV_ROPE || epilogue == EPI_QKV_ROPE_SPLIT) {
         if (!qkv || Nout % 256 != 0) return RADIX_ERR_UNSUPPORTED;
         qe = *qkv;
     }

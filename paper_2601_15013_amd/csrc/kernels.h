@@ -52,6 +52,8 @@ enum GemmEpilogue {
     EPI_SWIGLU = 2,    // W holds gate/up interleaved in blocks of 32 rows; out[M, Nout/2] = silu(gate) * up
     EPI_QKV_ROPE = 3,  // EPI_STORE of the fused q|k|v row with per-head RMSNorm and RoPE applied to q and k heads
     EPI_STORE_F32 = 4, // C stored as fp32 (16-bit operand GEMMs only; the fp32 GEMM's EPI_STORE already is fp32)
+    EPI_QKV_ROPE_SPLIT = 7, // EPI_QKV_ROPE with every q | k | v value y written as a 16-bit (hi, lo) pair: out[M, 2 Nout]
+                            // holds T(y) in columns [0, Nout) and T(y - T(y)) in columns [Nout, 2 Nout)
     EPI_RESIDUAL_NORM = 6, // EPI_RESIDUAL that also prepares the RMSNorm of the updated rows (NormFusion, producer side)
     EPI_SWIGLU_SPLIT = 5  // EPI_SWIGLU with the result y written as a 16-bit (hi, lo) pair: out[M, 2 (Nout/2)] holds
                           // T(y) in columns [0, Nout/2) and T(y - T(y)) in columns [Nout/2, Nout)
@@ -108,8 +110,10 @@ void launch_attention_f32(const float* qkv, const int32_t* cu, int B, int N, int
                           int n_kv_heads, int hd, float* out, hipStream_t stream);
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), head_dim 128.
 // split_out != 0: out is [N, 2 dq] and a row holds T(o) in columns [0, dq) and T(o - T(o)) in columns [dq, 2 dq).
+// split_in != 0: qkv is [N, 2 (dq + 2 dkv)], a row holds q | k | v (hi parts) and then q | k | v (lo parts).
 int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int max_seqlen, int n_q_heads,
-                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out = 0);
+                          int n_kv_heads, int hd, void* out, int op_dtype, hipStream_t stream, int split_out = 0,
+                          int split_in = 0);
 // The same attention with scatter and gather folded in: q | k | v rows are read from the COMPACT buffer
 // qkv_c[n_compact, dq + 2 dkv] through I_scatter, only the representative positions of a sequence are computed,
 // and their rows go straight to out_c[n_compact, dq] (split_out: [n_compact, 2 dq], hi | lo).  The work list
@@ -117,7 +121,7 @@ int launch_attention_mfma(const void* qkv, const int32_t* cu, int B, int N, int 
 int launch_attention_mfma_fused(const void* qkv_c, const int32_t* cu, const int32_t* I_scatter,
                                 const int32_t* plan, int B, int N, int n_compact, int n_q_heads,
                                 int n_kv_heads, int hd, void* out_c, int op_dtype, hipStream_t stream,
-                                int split_out = 0);
+                                int split_out = 0, int split_in = 0);
 
 // Work list of the fused attention kernel, built once per forward.  The representative positions of sequence
 // b are its tail [first_b, len_b) (first_b: the first position whose token is its own representative); they are

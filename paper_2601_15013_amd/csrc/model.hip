@@ -114,8 +114,8 @@ WsLayout ws_layout(const radix_model_config& c, int hilo_layers, size_t N, size_
     L.ss = take(M * ((size_t)c.d / 128 + 1) * 4);      // per-row sums of squares in 128-column slots (RMSNorm folded into the GEMMs)
     const size_t w2 = hilo_layers > 0 ? 2 : 1;     // (hi, lo) rows are twice as wide
     L.a = take(M * c.d * es * w2);
-    L.qkv = take(M * row * es);
-    L.qkv_full = take(N * row * es);
+    L.qkv = take(M * row * es * w2);
+    L.qkv_full = take(N * row * es * w2);
     L.attn_full = take(N * dq * es * w2);
     L.attn_c = take(M * dq * es * w2);
     L.mlp = take(M * (size_t)c.d_int * es * w2);
@@ -318,7 +318,8 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
     fused = fused && dedup && c.compute_dtype != RADIX_F32;   // the fused kernel is the MFMA one
     // the fused kernel addresses the compact q|k|v buffer with 32-bit byte offsets; beyond 4 GB the three-kernel
     // path (same results) takes over
-    if (fused && (long long)M * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * (long long)esize(c.compute_dtype) >= (1LL << 32))
+    if (fused && (long long)M * (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim * (long long)esize(c.compute_dtype) *
+                     (model->hilo_layers > 0 ? 2 : 1) >= (1LL << 32))
         fused = false;
     const WsLayout L = ws_layout(c, model->hilo_layers, (size_t)N, (size_t)B);
     if (ws_bytes < L.total) return RADIX_ERR_WORKSPACE_TOO_SMALL;
@@ -402,14 +403,17 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
                 launch_rmsnorm(h, Lw.g1, M, d, c.eps, a, dt, stream);
             }
         }
-        // Q/K-norm and RoPE ride in the QKV GEMM's epilogue when a wavefront block is one head
+        // Q/K-norm and RoPE ride in the QKV GEMM's epilogue when a wavefront block is one head; in a (hi, lo) layer
+        // that epilogue also writes q, k and v as (hi, lo) pairs, which attention then multiplies term by term
         const bool fused_rope = dt != RADIX_F32 && hd == 128 && row % 256 == 0;
+        const bool qkv_split = hl && fused_rope;
+        const int q2 = qkv_split ? 2 : 1;
         {
             TimedScope t(t_qkv, stream);
             const QkvEpilogue qe = {Lw.gq, Lw.gk, model->cos_tab, model->sin_tab, pos_c,
                                     c.n_q_heads, c.n_kv_heads, c.qk_norm, c.eps};
-            rc = gemm(a, Lw.wqkv, row, w2 * d, d, fused_rope ? EPI_QKV_ROPE : EPI_STORE, qkv, fused_rope ? &qe : nullptr,
-                      nullptr, folded1 ? &consume : nullptr);
+            rc = gemm(a, Lw.wqkv, row, w2 * d, d, qkv_split ? EPI_QKV_ROPE_SPLIT : (fused_rope ? EPI_QKV_ROPE : EPI_STORE), qkv,
+                      fused_rope ? &qe : nullptr, nullptr, folded1 ? &consume : nullptr);
             if (rc != RADIX_OK) return rc;
         }
         if (!fused_rope) {
@@ -421,7 +425,7 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         if (fused) {   // scatter, attention and gather in one kernel (exact): compact rows in, compact rows out
             TimedScope t(RADIX_TIME_ATTENTION, stream);
             rc = launch_attention_mfma_fused(qkv, cu, Is, plan, B, N, M_valid, c.n_q_heads, c.n_kv_heads, hd, attn_c,
-                                             dt, stream, hl);
+                                             dt, stream, hl, qkv_split);
             if (rc != RADIX_OK) return rc;
             if (M > M_valid)    // padding rows: any defined value will do, they only feed rows nobody reads
                 launch_index_select_rows(attn_c, M_valid, nullptr, M - M_valid, attn_row_bytes,
@@ -429,13 +433,13 @@ int forward_impl(const radix_model* model, const int32_t* tok, const int32_t* po
         }
         if (dedup && !fused) {   // Scatter(q), Scatter(k), Scatter(v): one row copy of the fused q|k|v row
             TimedScope t(RADIX_TIME_SCATTER, stream);
-            launch_index_select_rows(qkv, M_valid, Is, N, (size_t)row * es, qkv_full, hdr, stream);
+            launch_index_select_rows(qkv, M_valid, Is, N, (size_t)q2 * row * es, qkv_full, hdr, stream);
         }
         if (!fused) {
             TimedScope t(RADIX_TIME_ATTENTION, stream);
             if (dt != RADIX_F32) {
                 rc = launch_attention_mfma(qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd, attn_full,
-                                           dt, stream, hl);
+                                           dt, stream, hl, qkv_split);
                 if (rc != RADIX_OK) return rc;
             } else {
                 launch_attention_f32((const float*)qkv_full, cu, B, N, max_seqlen, c.n_q_heads, c.n_kv_heads, hd,

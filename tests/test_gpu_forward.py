@@ -303,8 +303,8 @@ def test_c3_full_size_sampled_sequences():
 
 def test_c4_full_size_sampled_sequences():
     # 8B shape, 256 sequences, eight of them spread over the batch.  With N(0, 0.02) weights at d = 4096 a projection
-    # has gain 0.02 * sqrt(4096) = 1.28: the library finds that from the weights and runs its first layers with
-    # (hi, lo) GEMM inputs (plain fp16 operands everywhere measure 2.1e-2 here)
+    # has gain 0.02 * sqrt(4096) = 1.28: the library finds that from the weights and runs its first layer with
+    # (hi, lo) pairs at every rounding point (plain fp16 operands everywhere measure 2.1e-2 here)
     _sampled_parity("C4", [0, 37, 74, 111, 148, 185, 222, 255])
 
 

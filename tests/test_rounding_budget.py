@@ -9,8 +9,9 @@ path is involved) and checks the three statements the library's precision settin
      2e-2 bar, which is why fp16 operands (11 bits) are the default and bf16 operands carry no parity claim;
   2. on a deep model whose projections do not attenuate (gain rms(W) sqrt(d) >= 1), most of the final error is
      made in layer 0, whose outputs are the whole residual stream at that depth;
-  3. carrying the four GEMM inputs (a, b, o, m) of the first two layers as (hi, lo) pairs removes about a third
-     of the error for 2 / n_layers more GEMM work: the automatic hilo_layers setting.
+  3. carrying all six points of layer 0 as (hi, lo) pairs removes more than half of the error for 1 / n_layers more
+     GEMM work (the automatic hilo_layers setting); the four GEMM inputs (a, b, o, m) alone, even in two layers,
+     remove about a third.
 """
 import dataclasses
 import math
@@ -108,15 +109,18 @@ def test_first_layers_dominate_and_hilo_inputs_there_pay():
     f16 = dict.fromkeys(POINTS, "f16")
     exact = dict.fromkeys(POINTS)
     hilo = dict(f16, a="f16x2", b="f16x2", o="f16x2", m="f16x2")
+    hilo6 = dict.fromkeys(POINTS, "f16x2")
     mx_all, rms_all = case.err(lambda l: f16)
     mx_l0, rms_l0 = case.err(lambda l: f16 if l == 0 else exact)
     mx_rest, rms_rest = case.err(lambda l: exact if l == 0 else f16)
     mx_h2, rms_h2 = case.err(lambda l: hilo if l < 2 else f16)
     mx_hall, rms_hall = case.err(lambda l: hilo)
+    mx_6, rms_6 = case.err(lambda l: hilo6 if l == 0 else f16)
     print(f"gain-1.28 proxy, 36 layers, fp16 roundings: all layers rms {rms_all:.3e} (max {mx_all:.3e}); layer 0 only "
           f"{rms_l0:.3e}; all but layer 0 {rms_rest:.3e}; (hi, lo) a/b/o/m in layers 0-1 {rms_h2:.3e} (max {mx_h2:.3e}); "
-          f"in all layers {rms_hall:.3e}")
+          f"in all layers {rms_hall:.3e}; all six points (hi, lo) in layer 0 {rms_6:.3e} (max {mx_6:.3e})")
     assert rms_l0 > 0.75 * rms_all                  # layer 0 alone makes most of the error ...
     assert rms_rest < 0.65 * rms_all                # ... and the other 35 layers together much less
     assert rms_h2 < 0.75 * rms_all                  # two (hi, lo) layers: a third of the error gone
     assert rms_h2 < 1.25 * rms_hall                 # and most of what (hi, lo) inputs in every layer would give
+    assert rms_6 < 0.55 * rms_all                   # all six points in layer 0 alone: more than half of the error gone
