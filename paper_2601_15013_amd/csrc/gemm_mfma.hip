@@ -8,8 +8,8 @@
 // lane (r = lane % 32, g = lane / 32) supplies 8 consecutive k of row r for k-group g.
 //
 // Structure
-//   * Workgroup tile BM x BN, k-tile 32, 256 threads = 4 wavefronts in a WAVES_M x WAVES_N grid;
-//     each wavefront owns (BM/WAVES_M) x (BN/WAVES_N) outputs as 32x32 MFMA accumulators.
+//   * Workgroup tile BM x BN, k-tile 32, 4 or 8 wavefronts (one or two per SIMD) in a WAVES_M x WAVES_N
+//     grid; each wavefront owns (BM/WAVES_M) x (BN/WAVES_N) outputs as 32x32 MFMA accumulators.
 //   * The product is formed transposed, C^T = W * A^T (weights are the MFMA "A" operand), so a
 //     lane owns one output ROW and 4 consecutive columns per register quad: the fp32 epilogues
 //     (residual read-modify-write, plain fp32 store) access 16 bytes per lane straight from that
@@ -36,7 +36,6 @@
 namespace {
 
 constexpr int BK = 32;            // k-tile: 64 bytes = 4 chunks of 16 bytes per row
-constexpr int GEMM_THREADS = 256;
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt = imm[15:14|3:0],
 // expcnt = imm[6:4], lgkmcnt = imm[11:8]).
@@ -76,7 +75,7 @@ __device__ __forceinline__ int swz(int row) { return (row >> 2) & 3; }
 __device__ __forceinline__ int slot(int row, int c) { return row * 4 + (c ^ swz(row)); }
 
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename Op<DT>::T* __restrict__ A,
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(const typename Op<DT>::T* __restrict__ A,
                                                                  const typename Op<DT>::T* __restrict__ W, int M,
                                                                  int Nout, int K, void* __restrict__ out_,
                                                                  int tiles_m, int tiles_n, int w_k,
@@ -84,10 +83,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
-    static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts");
+    constexpr int NW = WAVES_M * WAVES_N;                      // wavefronts: 4 (one per SIMD) or 8 (two per SIMD)
+    static_assert(NW == 4 || NW == 8, "4 or 8 wavefronts");
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int MB = WTM / 32, NB = WTN / 32;
-    constexpr int A_LOADS = BM / 64, B_LOADS = BN / 64;        // 1 KB wave-loads per wavefront per k-tile
+    constexpr int A_LOADS = BM / (16 * NW), B_LOADS = BN / (16 * NW);   // 1 KB wave-loads per wavefront per k-tile
     constexpr int LOADS = A_LOADS + B_LOADS;
     constexpr int STAGE = (BM + BN) * 4;                       // 16-byte slots per stage
     constexpr bool SWIGLU = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_SPLIT;
@@ -96,10 +96,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     static_assert(!SWIGLU || (NB % 2 == 0), "SwiGLU needs gate/up block pairs in one wavefront");
     static_assert(!ROPE || WTN == 128, "Q/K-norm + RoPE epilogue: one wavefront = one 128-wide head");
     static_assert(EPI != EPI_RESIDUAL_NORM || WTN == 128, "sum-of-squares slots are 128 columns = one wavefront");
-    static_assert(LOADS * 2 + (BM / 64) * 2 < 64, "vmcnt range");
+    static_assert(LOADS * 2 + A_LOADS * 2 < 64, "vmcnt range");
 
     constexpr int EPI_PITCH = 272;                             // epilogue row pitch in bytes (256 + 16 pad)
-    constexpr int EPI_SLOTS = 4 * 64 * EPI_PITCH / 16;         // 4 wavefronts x 64 rows
+    constexpr int EPI_SLOTS = NW * 64 * EPI_PITCH / 16;        // 64 rows per wavefront
     // ring of k-tile stages: six where they fit the 160 KB of LDS (the smaller tiles), else five
     constexpr int NS = (6 * STAGE * 16 <= 160 * 1024) ? 6 : 5;
     constexpr int LDS_SLOTS = NS * STAGE > EPI_SLOTS ? NS * STAGE : EPI_SLOTS;
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     const int r = lane & 31, g = lane >> 5;
 
     // ---- global-load assignment.  Wave-load j of this wavefront fills tile rows
-    // [16 (wave + 4 j), +16): lane L -> row + L / 4, LDS chunk L % 4, global chunk (L % 4) ^ swz(row).
+    // [16 (wave + NW j), +16): lane L -> row + L / 4, LDS chunk L % 4, global chunk (L % 4) ^ swz(row).
     // Addresses are (uniform 64-bit tile base, advanced per k-tile) + (per-lane 32-bit byte offset).
     // With a row map (amap.rows != nullptr) row m of the product is row amap.rows[m] of A: the gather in front
     // of the output projection rides in these offsets instead of being a copy kernel of its own.  Rows at or
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     uint32_t a_off[A_LOADS], w_off[B_LOADS];
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
-        const int row = 16 * (wave + 4 * j) + lrow;
+        const int row = 16 * (wave + NW * j) + lrow;
         int src = row < m_last ? row : m_last;
         if (amap.rows != nullptr) {
             const int m = m0 + src;
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     }
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j) {
-        const int row = 16 * (wave + 4 * j) + lrow;
+        const int row = 16 * (wave + NW * j) + lrow;
         w_off[j] = (uint32_t)(((size_t)row * w_k + 8 * (lpc ^ swz(row))) * sizeof(T));
     }
     const char* a_base = (const char*)(A + (amap.rows != nullptr ? (size_t)0 : (size_t)m0 * K));
@@ -231,11 +231,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_mfma_kernel(const typename 
     do {                                                                                                           \
         if ((F) < A_LOADS)                                                                                         \
             dma16(a_base + (size_t)(KT_) * (BK * sizeof(T)), a_off[(F) < A_LOADS ? (F) : 0],                       \
-                  lds_base + (SO) + 1024 * (wave + 4 * (F)));                                                      \
+                  lds_base + (SO) + 1024 * (wave + NW * (F)));                                                      \
         else if ((F) < LOADS)                                                                                      \
             dma16(w_base + (size_t)((KT_) >= WKT ? (KT_) - WKT : (KT_)) * (BK * sizeof(T)),                        \
                   w_off[(F) >= A_LOADS && (F) < LOADS ? (F) - A_LOADS : 0],                                        \
-                  lds_base + (SO) + BM * 64 + 1024 * (wave + 4 * ((F) - A_LOADS)));                                \
+                  lds_base + (SO) + BM * 64 + 1024 * (wave + NW * ((F) - A_LOADS)));                                \
     } while (0)
 
     // loads of k-tiles T0 and T0+1, row group by row group: the two 64-byte halves of every 128-byte
@@ -673,7 +673,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     typedef typename Op<DT>::T T;
     if (Nout % BN != 0 || K % (2 * BK) != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
-    dim3 grid((unsigned)(tiles_m * tiles_n)), block(GEMM_THREADS);
+    dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WAVES_M * WAVES_N);
 #define RADIX_LAUNCH(E)                                                                                       \
     do {                                                                                                      \
         auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
@@ -686,7 +686,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     else if (epilogue == EPI_SWIGLU_SPLIT) RADIX_LAUNCH(EPI_SWIGLU_SPLIT);
     else if (epilogue == EPI_STORE_F32) RADIX_LAUNCH(EPI_STORE_F32);
     else if (epilogue == EPI_RESIDUAL_NORM) {
-        if constexpr (BN / WAVES_N == 128) RADIX_LAUNCH(EPI_RESIDUAL_NORM);
+        if constexpr (BN / WAVES_N == 128 && WAVES_M * WAVES_N == 4) RADIX_LAUNCH(EPI_RESIDUAL_NORM);
         else return RADIX_ERR_UNSUPPORTED;
     }
     else if (epilogue == EPI_QKV_ROPE) {
@@ -704,9 +704,11 @@ template <int DT>
 int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int epilogue, void* out, int variant,
               const QkvEpilogue& qe, const ARowMap& amap, const NormFusion& nf, hipStream_t stream) {
     // Tile choice by a small cost model: workgroups run one per CU in rounds, a round costs a fixed part
-    // (launch, first loads, epilogue) plus the k-tiles at the rate measured for that tile shape
-    // (microseconds per 32-wide k-tile on MI355X, random fp16 operands): a launch that does not fill its
-    // last round pays for it in full, which is what decides between the shapes for small M * Nout.
+    // (launch, first loads, epilogue) plus the k-tiles at the rate measured for that shape (microseconds per
+    // 32-wide k-tile on MI355X, random fp16 operands): a launch that does not fill its last round pays for it
+    // in full, which is what decides between the shapes for small M * Nout.  Eight wavefronts (two per SIMD,
+    // 256 registers each) lose nothing in the main loop and overlap each other's epilogue and first loads:
+    // 1 to 4 us less per round; with four wavefronts the k-tiles of very long K run a touch faster.
     if (variant == 0) {
         static int n_cu = 0;
         if (n_cu == 0) {
@@ -716,13 +718,17 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int
                 cus = 256;
             n_cu = cus;
         }
-        struct Shape { int variant, bm, bn; double fixed_us, ktile_us; };
-        static const Shape shapes[3] = {{1, 256, 256, 9.0, 0.83}, {3, 128, 256, 7.0, 0.57}, {2, 128, 128, 5.0, 0.29}};
+        struct Shape { int variant, bm, bn, wave_cols; double fixed_us, ktile_us; };
+        static const Shape shapes[5] = {{4, 256, 256, 128, 8.0, 0.835}, {1, 256, 256, 128, 9.0, 0.83},
+                                        {5, 128, 256, 64, 6.5, 0.54},   {3, 128, 256, 128, 7.0, 0.57},
+                                        {2, 128, 128, 64, 5.0, 0.29}};
         double best = 0.0;
         for (const Shape& sh : shapes) {
             if (Nout % sh.bn != 0) continue;
-            if ((epilogue == EPI_QKV_ROPE || epilogue == EPI_QKV_ROPE_SPLIT || epilogue == EPI_RESIDUAL_NORM) && sh.bn != 256)
+            if ((epilogue == EPI_QKV_ROPE || epilogue == EPI_QKV_ROPE_SPLIT || epilogue == EPI_RESIDUAL_NORM) &&
+                sh.wave_cols != 128)
                 continue;                                            // need 128-wide wavefront blocks
+            if (epilogue == EPI_RESIDUAL_NORM && sh.variant == 4) continue;   // that epilogue needs 512 registers
             const double tiles = (double)ceil_div(M, sh.bm) * (Nout / sh.bn);
             double rounds = tiles / n_cu;
             if (rounds < 8.0) rounds = (double)(long long)(rounds + 0.999999);   // few rounds: the last one counts whole
@@ -731,6 +737,8 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int
         }
         if (variant == 0) return RADIX_ERR_UNSUPPORTED;
     }
+    if (variant == 5 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 4>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
+    if (variant == 4 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 4, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
     if (variant == 1 && Nout % 256 == 0) return launch_cfg<DT, 256, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
     if (variant == 3 && Nout % 256 == 0) return launch_cfg<DT, 128, 256, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
     return launch_cfg<DT, 128, 128, 2, 2>(A, W, M, Nout, K, w_k, epilogue, out, qe, amap, nf, stream);
