@@ -413,10 +413,10 @@ def cpu_baseline(batch, weights, budget_s):
     lens = [int(batch.cu_seqlens[s + 1] - batch.cu_seqlens[s]) for s in range(batch.B)]
     # sample size from a rough rate (fp64 matmuls on ~16 cores: a few hundred GFLOP/s), at least one sequence
     flops_tok = cfg.n_layers * (2.0 * cfg.d * (cfg.dq + 2 * cfg.dkv) + 2.0 * cfg.dq * cfg.d + 6.0 * cfg.d * cfg.d_int)
-    want_tokens = budget_s * 3e11 / flops_tok
+    want_tokens = budget_s * 4e11 / flops_tok
     seqs, tokens = [], 0
     for s in range(batch.B):
-        if seqs and tokens + lens[s] > want_tokens:
+        if tokens >= want_tokens:
             break
         if lens[s] > 0:
             seqs.append(s)
