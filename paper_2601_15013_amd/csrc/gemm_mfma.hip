@@ -79,7 +79,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(const
                                                                  const typename Op<DT>::T* __restrict__ W, int M,
                                                                  int Nout, int K, void* __restrict__ out_,
                                                                  int tiles_m, int tiles_n, int w_k,
-                                                                 QkvEpilogue qe, ARowMap amap, NormFusion nf) {
+                                                                 QkvEpilogue qe, ARowMap amap, NormFusion nf, int BAND) {
     typedef typename Op<DT>::T T;
     typedef typename Op<DT>::V8 V8;
     typedef typename Op<DT>::V4 V4;
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(const
     constexpr int LDS_SLOTS = NS * STAGE > EPI_SLOTS ? NS * STAGE : EPI_SLOTS;
     __shared__ uint4 lds_all[LDS_SLOTS];
 
-    // ---- tile assignment: XCD-aware renumbering, then row-tile bands of 8 sweeping the columns
+    // ---- tile assignment: XCD-aware renumbering, then bands of BAND row tiles sweeping the columns
     int pid = blockIdx.x;
     {
         const int nblk = tiles_m * tiles_n;
@@ -113,7 +113,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(const
         const int x = pid % 8, q = pid / 8;
         pid = x * per + (x < rem ? x : rem) + q;
     }
-    constexpr int BAND = 8;
     const int band = pid / (BAND * tiles_n);
     const int band_rows = (tiles_m - band * BAND) < BAND ? (tiles_m - band * BAND) : BAND;
     const int in_band = pid - band * BAND * tiles_n;
@@ -674,11 +673,21 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     if (Nout % BN != 0 || K % (2 * BK) != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
     dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WAVES_M * WAVES_N);
+    // Row tiles per band (see the kernel's tile assignment).  The 32 workgroups an XCD runs at a time cover
+    // band x (32 / band) tiles, i.e. band + 32 / band operand strips stream through its L2: 12 for a band of 4
+    // or 8, 18 for 2.  The activation strips of a band are read again for every group of column tiles, and what
+    // serves those re-reads is the 256 MB memory-side cache shared by all XCDs: the eight bands in flight must
+    // leave room in it for the weights, so long rows (large K) take a narrower band.  Measured on MI355X, us per
+    // launch with bands of 8 / 4 / 2 / 1: M 45120, N 4096, K 12288: 4210 / 4168 / 4134 / 4109; N 24576, K 4096:
+    // 7109 / 7025 / 7105 / 7821; N 6144, K 4096: 1827 / 1841 / 1840 / 1929.
+    int band_cfg = 8;
+    while (band_cfg > 1 && 8.0 * band_cfg * BM * (double)K * sizeof(T) > 64.0 * 1024 * 1024) band_cfg /= 2;
+    if (band_cfg == 1 && tiles_n > 16) band_cfg = 2;          // one row of many column tiles: 33 strips per group
 #define RADIX_LAUNCH(E)                                                                                       \
     do {                                                                                                      \
         auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
         hipLaunchKernelGGL(kfn, grid, block, 0, stream, (const T*)A, (const T*)W, M, Nout, K, out, tiles_m,   \
-                           tiles_n, w_k, qe, amap, nf);                                                       \
+                           tiles_n, w_k, qe, amap, nf, band_cfg);                                             \
     } while (0)
     if (epilogue == EPI_STORE) RADIX_LAUNCH(EPI_STORE);
     else if (epilogue == EPI_RESIDUAL) RADIX_LAUNCH(EPI_RESIDUAL);
