@@ -203,6 +203,13 @@ def main() -> int:
     gemm_ms = sum(per_kernel[k][0] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_hilo_layers"))
     lens = np.diff(batch.cu_seqlens).astype(np.float64)
     attn_flops = float(np.sum(2.0 * cfg.n_q_heads * cfg.head_dim * (lens * lens + lens))) * cfg.n_layers
+    if fused and n_c < N:
+        # the fused kernel computes the rows the gather keeps: per sequence the positions from its first
+        # representative on (in a trie the representatives of a sequence are a suffix of it)
+        g = I_g[:n_c].cpu().numpy().astype(np.int64)
+        per_seq = np.bincount(np.searchsorted(batch.cu_seqlens[1:], g, side="right"), minlength=batch.B).astype(np.float64)
+        first = lens - per_seq
+        attn_flops = float(np.sum(2.0 * cfg.n_q_heads * cfg.head_dim * ((lens * lens + lens) - (first * first + first)))) * cfg.n_layers
     es = 2 if cfg.dtype != "f32" else 4
     scatter_bytes = (n_c + N) * (dq + 2 * dkv) * es
     gather_bytes = 2 * n_c * dq * es
@@ -238,6 +245,7 @@ def main() -> int:
         "kernel_ms_per_forward": {k: v[0] for k, v in per_kernel.items()},
         "compact_gemm_tflops": gemm_flops_layer * cfg.n_layers / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else None,
         "compact_gemm_frac_of_peak": (gemm_flops_layer * cfg.n_layers / (gemm_ms * 1e-3) / 1e12 / peak) if gemm_ms > 0 else None,
+        "attention_tflops_note": "algorithmic flop of the query rows the running attention mode computes (all N rows, or the representative rows in the fused mode) over the attention kernel time",
         "attention_tflops": attn_flops / (per_kernel["attention"][0] * 1e-3) / 1e12 if per_kernel["attention"][0] > 0 else None,
         "scatter_GBps": scatter_bytes * cfg.n_layers / (per_kernel["scatter"][0] * 1e-3) / 1e9 if per_kernel["scatter"][0] > 0 else None,
         "gather_GBps": gather_bytes * cfg.n_layers / (per_kernel["gather"][0] * 1e-3) / 1e9 if per_kernel["gather"][0] > 0 else None,
