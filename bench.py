@@ -85,6 +85,9 @@ def main() -> int:
                     help="also time the LM head (tied to the embedding) on the last token of every sequence, outside "
                          "the timed steps; reported as lm_head_last_token")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default run (C4) only: skip the short runs of C2, C3, C5 and C5ctl that are reported beside "
+                         "the headline as other_workloads")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="rough budget of the oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -269,8 +272,56 @@ def main() -> int:
         result["cpu_baseline"] = cpu_baseline(batch, weights, args.cpu_seconds)
 
     model.close()
+    if key == "C4" and not args.no_other_workloads and not args.three_kernel_attention and not args.fold_norms \
+            and args.hilo_layers == 0:
+        del model, run, out, I_s, I_g, tok, cu, weights, batch
+        torch.cuda.empty_cache()
+        result["other_workloads"] = {k: short_run(k, torch, binding, harness, synth) for k in ("C2", "C3", "C5", "C5ctl")}
     print(json.dumps(result))
     return 0
+
+
+def short_run(key, torch, binding, harness, synth):
+    """A named workload with the library's defaults, timed briefly: the same step as the headline (index build +
+    deduplicated forward) and the no-dedup forward on the same batch."""
+    batch, weights = synth.make_batch(key), synth.make_weights(key)
+    cfg = weights.cfg
+    model = harness.upload_model(weights)
+    run = harness.Runner(model, batch.N, batch.B)
+    tok, cu = harness.upload_batch(batch)
+    N, max_len = batch.N, batch.max_seqlen
+    out = torch.empty((N, cfg.d), dtype=torch.float32, device="cuda")
+    I_s = torch.empty(N, dtype=torch.int32, device="cuda")
+    I_g = torch.empty(N, dtype=torch.int32, device="cuda")
+    n_dev = torch.empty(1, dtype=torch.int32, device="cuda")
+    force = key == "C5ctl"
+    n_c = [0]
+
+    def step():
+        maps = binding.radix_build_index(tok, None, cu, run.ws, I_s, I_g, n_dev)
+        binding.radix_prefill_forward(model, tok, None, cu, max_len, maps[0], maps[1], maps[3], run.ws, out=out,
+                                      force_dedup=force)
+        n_c[0] = maps[3]
+
+    def timed(fn, iters):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / iters
+
+    step()
+    iters = 20 if N * cfg.n_layers * cfg.d * cfg.d_int < 3e15 else 4
+    ms = timed(step, iters)
+    ms_nd = timed(lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, max_len, run.ws, out=out),
+                  max(2, iters // 4))
+    assert run.status() == 0
+    res = {"workload": WORKLOAD_TEXT[key], "N": N, "N_compact": n_c[0], "compression_r": N / max(n_c[0], 1),
+           "steps": iters, "ms_per_step": ms, "tokens_per_s": N / (ms * 1e-3), "forward_nodedup_ms": ms_nd,
+           "speedup_vs_nodedup_incl_build": ms_nd / ms, "hilo_layers": model.hilo_layers}
+    model.close()
+    return res
 
 
 def index_select_bench(args, torch, np, binding):
