@@ -29,7 +29,8 @@
 //     give bit-identical rows.
 //   * Ragged M: rows >= M are fetched from row M-1 and never stored.
 //   * Workgroups are numbered so that the 8 XCDs (round-robin dispatch) each work on a compact
-//     band of row tiles, sweeping the weight tiles, which keeps an XCD's L2 on few A rows.
+//     band of row tiles, sweeping the weight tiles in step with the other XCDs (details at the tile
+//     assignment), which keeps an XCD's L2 on few A rows and the shared memory-side cache on few W rows.
 #include "common.h"
 #include "kernels.h"
 
@@ -105,19 +106,39 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(const
     constexpr int LDS_SLOTS = NS * STAGE > EPI_SLOTS ? NS * STAGE : EPI_SLOTS;
     __shared__ uint4 lds_all[LDS_SLOTS];
 
-    // ---- tile assignment: XCD-aware renumbering, then bands of BAND row tiles sweeping the columns
-    int pid = blockIdx.x;
+    // ---- tile assignment.  Workgroup ids go round-robin to the 8 XCDs (own L2 each): XCD x runs ids x, x + 8, ...
+    // in order.  Row tiles are grouped in bands of BAND that sweep the column (weight) tiles.  While there are 8 whole
+    // bands left, each XCD takes one of them and all eight sweep the columns in step, so that a weight strip is
+    // asked for by all XCDs at about the same time and has to stay in the memory-side cache only that long; every
+    // other sweep runs backwards, starting on the weight strips used last.  The rows left over (fewer than 8 bands)
+    // are split evenly: each XCD gets a contiguous run of their tiles in band order.
+    int tm, tn;
     {
-        const int nblk = tiles_m * tiles_n;
-        const int per = nblk / 8, rem = nblk % 8;       // XCD x gets `per` (+1 if x < rem) blocks
-        const int x = pid % 8, q = pid / 8;
-        pid = x * per + (x < rem ? x : rem) + q;
+        const int x = blockIdx.x % 8, q = blockIdx.x / 8;
+        const int band_tiles = BAND * tiles_n;
+        const int S = tiles_m / (8 * BAND);                  // sweeps with one whole band per XCD
+        const int P1 = S * band_tiles;
+        int row0, band_rows, in_band;
+        if (q < P1) {
+            const int sidx = q / band_tiles;
+            in_band = q - sidx * band_tiles;
+            row0 = (sidx * 8 + x) * BAND;
+            band_rows = BAND;
+            tn = in_band / band_rows;
+            if (sidx & 1) tn = tiles_n - 1 - tn;
+        } else {
+            const int R = tiles_m - S * 8 * BAND;
+            const int nblk = R * tiles_n;
+            const int per = nblk / 8, rem = nblk % 8;       // XCD x gets `per` (+1 if x < rem) blocks
+            const int pid = x * per + (x < rem ? x : rem) + (q - P1);
+            const int band = pid / band_tiles;
+            band_rows = (R - band * BAND) < BAND ? (R - band * BAND) : BAND;
+            in_band = pid - band * band_tiles;
+            row0 = S * 8 * BAND + band * BAND;
+            tn = in_band / band_rows;
+        }
+        tm = row0 + in_band % band_rows;
     }
-    const int band = pid / (BAND * tiles_n);
-    const int band_rows = (tiles_m - band * BAND) < BAND ? (tiles_m - band * BAND) : BAND;
-    const int in_band = pid - band * BAND * tiles_n;
-    const int tm = band * BAND + in_band % band_rows;
-    const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
