@@ -206,6 +206,7 @@ def main() -> int:
     gemm_ms = sum(per_kernel[k][0] for k in ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "gemm_hilo_layers"))
     lens = np.diff(batch.cu_seqlens).astype(np.float64)
     attn_flops = float(np.sum(2.0 * cfg.n_q_heads * cfg.head_dim * (lens * lens + lens))) * cfg.n_layers
+    attn_flops_all_rows = attn_flops
     if fused and n_c < N:
         # the fused kernel computes the rows the gather keeps: per sequence the positions from its first
         # representative on (in a trie the representatives of a sequence are a suffix of it)
@@ -240,6 +241,7 @@ def main() -> int:
         "step_breakdown_ms": {"build_index": t_build, "forward_dedup": t_fwd, "forward_nodedup": t_nodedup},
         "speedup_vs_nodedup": t_nodedup / t_fwd,
         "speedup_vs_nodedup_incl_build": t_nodedup / (t_fwd + t_build),
+        "amdahl_model": amdahl_model(gemm_flops_layer / max(n_c, 1) * cfg.n_layers, N, n_c, attn_flops_all_rows, attn_flops),
         "nodedup_tokens_per_s": N / (t_nodedup * 1e-3),
         "other_attention_mode": {"mode": "scatter -> attention -> gather" if fused else "fused",
                                  "ms_per_step": t_step_other, "value": N / (t_step_other * 1e-3),
@@ -279,6 +281,17 @@ def main() -> int:
         result["other_workloads"] = {k: short_run(k, torch, binding, harness, synth) for k in ("C2", "C3", "C5", "C5ctl")}
     print(json.dumps(result))
     return 0
+
+
+def amdahl_model(pw_flops_per_row, N, n_c, attn_flops_all_rows, attn_flops_computed):
+    """The paper's speedup model (Experiments, theoretical speedup model: speedup = 1 / ((1 - f_c) + f_c / r), f_c the
+    position-wise share of the flop) with the exact flop counts of this model shape and batch; and the same with
+    the attention flop of the rows the running attention mode computes (fewer than all rows in the fused mode)."""
+    pw_full, pw_compact = pw_flops_per_row * N, pw_flops_per_row * n_c
+    f_c = pw_full / (pw_full + attn_flops_all_rows)
+    r = N / max(n_c, 1)
+    return {"f_c": f_c, "expected_speedup": 1.0 / ((1.0 - f_c) + f_c / r),
+            "expected_speedup_this_attention_mode": (pw_full + attn_flops_all_rows) / (pw_compact + attn_flops_computed)}
 
 
 def short_run(key, torch, binding, harness, synth):
