@@ -273,10 +273,15 @@ def main() -> int:
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(batch, weights, args.cpu_seconds)
 
+    others = key == "C4" and not args.no_other_workloads and not args.three_kernel_attention and not args.fold_norms \
+        and args.hilo_layers == 0
+    if others:
+        del run, out, I_s, I_g, tok, cu
+        torch.cuda.empty_cache()
+        result["paper_sweep_2048_256"] = paper_sweep_point(model, cfg, torch, binding, harness, synth)   # 8B shape
     model.close()
-    if key == "C4" and not args.no_other_workloads and not args.three_kernel_attention and not args.fold_norms \
-            and args.hilo_layers == 0:
-        del model, run, out, I_s, I_g, tok, cu, weights, batch
+    if others:
+        del model, weights, batch
         torch.cuda.empty_cache()
         result["other_workloads"] = {k: short_run(k, torch, binding, harness, synth) for k in ("C2", "C3", "C5", "C5ctl")}
     print(json.dumps(result))
@@ -292,6 +297,27 @@ def amdahl_model(pw_flops_per_row, N, n_c, attn_flops_all_rows, attn_flops_compu
     r = N / max(n_c, 1)
     return {"f_c": f_c, "expected_speedup": 1.0 / ((1.0 - f_c) + f_c / r),
             "expected_speedup_this_attention_mode": (pw_full + attn_flops_all_rows) / (pw_compact + attn_flops_computed)}
+
+
+def paper_sweep_point(model, cfg, torch, binding, harness, synth, prefix=2048, suffix=256):
+    """One point of the paper's sweep (Experiments, forward-pass benchmark: B = 32, shared prefix + distinct suffixes;
+    2048 / 256 is the point its speedup-model table quotes) on a model that is already uploaded: forward time with the
+    library's defaults, with Algorithm 1's three-kernel attention, and without deduplication; index build not
+    counted, as in the paper."""
+    batch = synth.shared_prefix_batch(SWEEP_SEED, 32, prefix, suffix, suffix, cfg.vocab, name="sweep")
+    run = harness.Runner(model, batch.N, batch.B)
+    tok, cu = harness.upload_batch(batch)
+    out = torch.empty((batch.N, cfg.d), dtype=torch.float32, device="cuda")
+    I_s, I_g, _, n_c = binding.radix_build_index(tok, None, cu, run.ws)
+    fwd = lambda mode: binding.radix_prefill_forward(model, tok, None, cu, batch.max_seqlen, I_s, I_g, n_c, run.ws,
+                                                     out=out, fused_attention=mode)
+    t_nd = _time_ms(torch, lambda: binding.radix_prefill_forward_nodedup(model, tok, None, cu, batch.max_seqlen, run.ws,
+                                                                          out=out), 3, 1)
+    t_def = _time_ms(torch, lambda: fwd(None), 3, 1)
+    t_3k = _time_ms(torch, lambda: fwd(False), 3, 1) if model.compute_dtype != "f32" else t_def
+    assert run.status() == 0
+    return {"prefix": prefix, "suffix": suffix, "N": batch.N, "N_compact": n_c, "nodedup_ms": t_nd, "dedup_ms": t_def,
+            "speedup": t_nd / t_def, "three_kernel_attention_ms": t_3k, "three_kernel_attention_speedup": t_nd / t_3k}
 
 
 def short_run(key, torch, binding, harness, synth):
@@ -333,6 +359,9 @@ def short_run(key, torch, binding, harness, synth):
     res = {"workload": WORKLOAD_TEXT[key], "N": N, "N_compact": n_c[0], "compression_r": N / max(n_c[0], 1),
            "steps": iters, "ms_per_step": ms, "tokens_per_s": N / (ms * 1e-3), "forward_nodedup_ms": ms_nd,
            "speedup_vs_nodedup_incl_build": ms_nd / ms, "hilo_layers": model.hilo_layers}
+    if key in ("C2", "C3"):          # the 0.6B and 4B model shapes are on the GPU now
+        del out, I_s, I_g, run
+        res["paper_sweep_2048_256"] = paper_sweep_point(model, cfg, torch, binding, harness, synth)
     model.close()
     return res
 
