@@ -129,7 +129,7 @@ enum { RADIX_ATTN_AUTO = 0, RADIX_ATTN_THREE_KERNELS = 1, RADIX_ATTN_FUSED = 2 }
 typedef struct radix_fwd_opts {
     float threshold;      /* deduplicate iff n_compact < threshold * N; 1.0 = whenever anything is shared, 0.0 = never
                            * (the paper's radix_mlp_threshold).  Negative (RADIX_THRESHOLD_AUTO): the library decides, per
-                           * layer: the position-wise work saved, (N - N') * F / 1.1e15 s (F = projection + MLP flops of
+                           * batch: the position-wise work saved per layer, (N - N') * F / 1.1e15 s (F = projection + MLP flops of
                            * one row), against what deduplication adds - with the fused attention kernel about 15 % of
                            * the attention time, 0.15 * 2 * dq * N * (N / B) / 5e14 s; with the three-kernel attention the
                            * scatter of (N' + N) q|k|v rows at 5e12 bytes/s.  (Rates: what the kernels reach on an
@@ -245,6 +245,18 @@ int radix_prefill_forward(const radix_model* model, const int32_t* tok, const in
                           const int32_t* I_scatter, const int32_t* I_gather, int32_t n_compact,
                           const radix_fwd_opts* opts, float* out,
                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * radix_dedup_decision - whether radix_prefill_forward would take the deduplicated path for a batch of B sequences,
+ * N tokens and n_compact unique rows on a model of this configuration with these options (NULL = the defaults): the
+ * rule documented at radix_fwd_opts.threshold (paper: Experiments, radix_mlp_threshold; Limitations,
+ * "Low-redundancy batches").  Host arithmetic only: no GPU is touched, `config` is a host pointer, *dedup_out is set
+ * to 1 or 0.  Errors: RADIX_ERR_NULL_POINTER, RADIX_ERR_BAD_SIZE (negative sizes, n_compact > N), the configuration
+ * errors of radix_model_create, RADIX_ERR_BAD_CONFIG / RADIX_ERR_UNSUPPORTED for the attention mode as in
+ * radix_prefill_forward.
+ */
+int radix_dedup_decision(const radix_model_config* config, int32_t B, int32_t N, int32_t n_compact,
+                         const radix_fwd_opts* opts, int32_t* dedup_out);
 
 /*
  * radix_prefill_forward_nodedup - the ordinary prefill over all N rows with the same kernels and

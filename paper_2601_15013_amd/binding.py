@@ -21,6 +21,7 @@ _DTYPES = {"f32": RADIX_F32, "bf16": RADIX_BF16, "f16": RADIX_F16}
 EXPORTS = (
     "radix_model_create", "radix_model_destroy", "radix_model_hilo_layers", "radix_index_workspace_bytes", "radix_workspace_bytes",
     "radix_build_index", "radix_build_index_static", "radix_prefill_forward", "radix_prefill_forward_nodedup",
+    "radix_dedup_decision",
     "radix_lm_head_workspace_bytes", "radix_lm_head",
     "radix_index_select_rows", "radix_device_status", "radix_status_string",
     "radix_timing_enable", "radix_timing_collect",
@@ -78,6 +79,8 @@ def _lib() -> C.CDLL:
         lib.radix_prefill_forward.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, C.POINTER(radix_fwd_opts),
                                               vp, vp, sz, vp]
         lib.radix_prefill_forward_nodedup.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, sz, vp]
+        lib.radix_dedup_decision.argtypes = [C.POINTER(radix_model_config), i32, i32, i32, C.POINTER(radix_fwd_opts),
+                                             C.POINTER(i32)]
         lib.radix_index_select_rows.argtypes = [vp, i32, vp, i32, sz, vp, vp, vp]
         lib.radix_lm_head_workspace_bytes.argtypes = [vp, i32, C.POINTER(sz)]
         lib.radix_lm_head.argtypes = [vp, vp, i32, vp, i32, vp, vp, sz, vp]
@@ -251,6 +254,17 @@ def radix_prefill_forward(model: Model, tok: torch.Tensor, pos: Optional[torch.T
                                       _ptr(ws), ws.numel(), _stream(stream))
     _check(rc, "radix_prefill_forward")
     return out
+
+
+def radix_dedup_decision(config: radix_model_config, B: int, N: int, n_compact: int, threshold: Optional[float] = None,
+                         force_dedup: bool = False, fused_attention: Optional[bool] = None) -> bool:
+    """Would radix_prefill_forward deduplicate this batch?  Host arithmetic in the library, no GPU involved."""
+    mode = 0 if fused_attention is None else (2 if fused_attention else 1)
+    opts = radix_fwd_opts(-1.0 if threshold is None else threshold, int(force_dedup), mode, 0)
+    out = C.c_int32(-1)
+    _check(_lib().radix_dedup_decision(C.byref(config), B, N, n_compact, C.byref(opts), C.byref(out)),
+           "radix_dedup_decision")
+    return bool(out.value)
 
 
 def radix_prefill_forward_nodedup(model: Model, tok: torch.Tensor, pos: Optional[torch.Tensor],

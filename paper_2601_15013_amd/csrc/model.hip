@@ -515,6 +515,54 @@ int check_common(const radix_model* model, const int32_t* tok, const int32_t* cu
 
 }  // namespace
 
+// Whether the deduplicated path runs for a batch (paper: Experiments, radix_mlp_threshold; Limitations,
+// "Low-redundancy batches").  Host arithmetic only.
+static bool decide_dedup(const radix_model_config& c, int32_t B, int32_t N, int32_t n_compact, const radix_fwd_opts* opts,
+                         bool fused) {
+    const float threshold = opts ? opts->threshold : RADIX_THRESHOLD_AUTO;
+    if (opts && opts->force_dedup != 0) return true;
+    if (threshold >= 0.f) return (double)n_compact < (double)threshold * (double)N;
+    // automatic: the position-wise work of the N - N' rows saved against what deduplication adds per layer
+    const double dq = (double)c.n_q_heads * c.head_dim, dkv = (double)c.n_kv_heads * c.head_dim;
+    const double flops_row = 2.0 * c.d * (dq + 2 * dkv) + 2.0 * dq * c.d + 6.0 * (double)c.d * c.d_int;
+    const double gemm_rate = c.compute_dtype == RADIX_F32 ? 2.0e13 : 1.1e15;
+    const double saved = ((double)N - n_compact) * flops_row / gemm_rate;
+    double added;
+    if (fused) {
+        // the fused kernel starts every workgroup with two more dependent loads (work list, index map) and
+        // cuts query blocks where the representatives start, not at multiples of the key tile: about 15 % on
+        // top of the attention time when nothing is shared
+        const double attn_flops = 2.0 * dq * (double)N * ((double)N / (B > 0 ? B : 1));
+        added = 0.15 * attn_flops / 5.0e14;
+    } else {
+        // three-kernel attention: the scatter of (N' + N) q|k|v rows
+        added = ((double)N + n_compact) * (dq + 2 * dkv) * (double)esize(c.compute_dtype) / 5.0e12;
+    }
+    return n_compact < N && saved > added;
+}
+
+static int fused_mode(const radix_model_config& c, const radix_fwd_opts* opts, bool* fused) {
+    const int mode = opts ? opts->attention_mode : RADIX_ATTN_AUTO;
+    if (mode != RADIX_ATTN_AUTO && mode != RADIX_ATTN_THREE_KERNELS && mode != RADIX_ATTN_FUSED) return RADIX_ERR_BAD_CONFIG;
+    if (mode == RADIX_ATTN_FUSED && c.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;
+    *fused = mode == RADIX_ATTN_FUSED || (mode == RADIX_ATTN_AUTO && c.compute_dtype != RADIX_F32);
+    return RADIX_OK;
+}
+
+extern "C" int radix_dedup_decision(const radix_model_config* config, int32_t B, int32_t N, int32_t n_compact,
+                                    const radix_fwd_opts* opts, int32_t* dedup_out) {
+    if (!config || !dedup_out) return RADIX_ERR_NULL_POINTER;
+    if (B < 0 || N < 0 || n_compact < 0 || n_compact > N) return RADIX_ERR_BAD_SIZE;
+    const radix_model_config& c = *config;
+    int rc = check_config(c);
+    if (rc != RADIX_OK) return rc;
+    bool fused = false;
+    rc = fused_mode(c, opts, &fused);
+    if (rc != RADIX_OK) return rc;
+    *dedup_out = decide_dedup(c, B, N, n_compact, opts, fused) ? 1 : 0;
+    return RADIX_OK;
+}
+
 extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* tok, const int32_t* pos,
                                      const int32_t* cu_seqlens, int32_t B, int32_t N, int32_t max_seqlen,
                                      const int32_t* I_scatter, const int32_t* I_gather, int32_t n_compact,
@@ -523,37 +571,10 @@ extern "C" int radix_prefill_forward(const radix_model* model, const int32_t* to
     if (rc != RADIX_OK) return rc;
     if (n_compact < 0 || n_compact > N || (N > 0 && n_compact == 0)) return RADIX_ERR_BAD_SIZE;
     if (N > 0 && (!I_scatter || !I_gather)) return RADIX_ERR_NULL_POINTER;
-    const int mode = opts ? opts->attention_mode : RADIX_ATTN_AUTO;
-    if (mode != RADIX_ATTN_AUTO && mode != RADIX_ATTN_THREE_KERNELS && mode != RADIX_ATTN_FUSED) return RADIX_ERR_BAD_CONFIG;
-    if (mode == RADIX_ATTN_FUSED && model->cfg.compute_dtype == RADIX_F32) return RADIX_ERR_UNSUPPORTED;
-    const bool fused = mode == RADIX_ATTN_FUSED || (mode == RADIX_ATTN_AUTO && model->cfg.compute_dtype != RADIX_F32);
-    const float threshold = opts ? opts->threshold : RADIX_THRESHOLD_AUTO;
-    const bool force = opts ? opts->force_dedup != 0 : false;
-    bool dedup;
-    if (force) {
-        dedup = true;
-    } else if (threshold >= 0.f) {
-        dedup = (double)n_compact < (double)threshold * (double)N;
-    } else {
-        // automatic: the position-wise work of the N - N' rows saved against what deduplication adds per layer
-        const radix_model_config& c = model->cfg;
-        const double dq = (double)c.n_q_heads * c.head_dim, dkv = (double)c.n_kv_heads * c.head_dim;
-        const double flops_row = 2.0 * c.d * (dq + 2 * dkv) + 2.0 * dq * c.d + 6.0 * (double)c.d * c.d_int;
-        const double gemm_rate = c.compute_dtype == RADIX_F32 ? 2.0e13 : 1.1e15;
-        const double saved = ((double)N - n_compact) * flops_row / gemm_rate;
-        double added;
-        if (fused) {
-            // the fused kernel starts every workgroup with two more dependent loads (work list, index map) and
-            // cuts query blocks where the representatives start, not at multiples of the key tile: about 15 % on
-            // top of the attention time when nothing is shared
-            const double attn_flops = 2.0 * dq * (double)N * ((double)N / (B > 0 ? B : 1));
-            added = 0.15 * attn_flops / 5.0e14;
-        } else {
-            // three-kernel attention: the scatter of (N' + N) q|k|v rows
-            added = ((double)N + n_compact) * (dq + 2 * dkv) * (double)esize(c.compute_dtype) / 5.0e12;
-        }
-        dedup = n_compact < N && saved > added;
-    }
+    bool fused = false;
+    rc = fused_mode(model->cfg, opts, &fused);
+    if (rc != RADIX_OK) return rc;
+    const bool dedup = decide_dedup(model->cfg, B, N, n_compact, opts, fused);
     if (opts && opts->pad_compact_to < 0) return RADIX_ERR_BAD_CONFIG;
     const int pad_to = opts ? opts->pad_compact_to : 0;
     if (!dedup) n_compact = N;
