@@ -65,8 +65,8 @@ INDEX_SELECT_SHAPES = [(16000, 1024, 12000), (16000, 1024, 70000), (100000, 2048
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=8)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_TEXT),
                     help="default: C4, the largest of the named single-GPU configurations")
     ap.add_argument("--three-kernel-attention", action="store_true",
