@@ -738,7 +738,7 @@ int launch_dt(const void* A, const void* W, int M, int Nout, int K, int w_k, int
     // 32-wide k-tile on MI355X, random fp16 operands): a launch that does not fill its last round pays for it
     // in full, which is what decides between the shapes for small M * Nout.  Eight wavefronts (two per SIMD,
     // 256 registers each) lose nothing in the main loop and overlap each other's epilogue and first loads:
-    // 1 to 4 us less per round; the four-wavefront tile only pays at K > 10000.
+    // 1 to 4 us less per round; the four-wavefront tile is only chosen at K > 16000.
     if (variant == 0) {
         static int n_cu = 0;
         if (n_cu == 0) {
