@@ -36,6 +36,16 @@ enum {
 int radix_timing_enable(uint32_t category_mask, uint32_t every_nth);
 int radix_timing_collect(float* total_ms_host, int32_t* launches_host);
 
+/*
+ * Host-side views of the GEMM launch geometry, for tests (no GPU is touched).
+ * radix_debug_gemm_tile: the output tile (*tm, *tn) that workgroup `bid` of a launch of tiles_m x tiles_n
+ * workgroups computes when row tiles are grouped in bands of `band` - the same function the kernel calls.
+ * radix_debug_gemm_band: the band width the launcher picks for 16-bit operands, row tiles of tile_rows rows and
+ * rows of K elements (>= 1), or a negative status.
+ */
+int radix_debug_gemm_tile(int32_t bid, int32_t tiles_m, int32_t tiles_n, int32_t band, int32_t* tm, int32_t* tn);
+int radix_debug_gemm_band(int32_t tile_rows, int32_t K, int32_t tiles_n);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = (
     "radix_dedup_decision",
     "radix_lm_head_workspace_bytes", "radix_lm_head",
     "radix_index_select_rows", "radix_device_status", "radix_status_string",
-    "radix_timing_enable", "radix_timing_collect",
+    "radix_timing_enable", "radix_timing_collect", "radix_debug_gemm_tile", "radix_debug_gemm_band",
 )
 
 TIMING_CATEGORIES = ("gemm_qkv", "gemm_o", "gemm_gateup", "gemm_down", "attention", "scatter", "gather", "rowops",
@@ -87,6 +87,8 @@ def _lib() -> C.CDLL:
         lib.radix_device_status.argtypes = [vp, sz, vp]
         lib.radix_timing_enable.argtypes = [C.c_uint32, C.c_uint32]
         lib.radix_timing_collect.argtypes = [C.POINTER(C.c_float), C.POINTER(i32)]
+        lib.radix_debug_gemm_tile.argtypes = [i32, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+        lib.radix_debug_gemm_band.argtypes = [i32, i32, i32]
         lib.radix_status_string.argtypes = [C.c_int]
         lib.radix_status_string.restype = C.c_char_p
         for n in EXPORTS:

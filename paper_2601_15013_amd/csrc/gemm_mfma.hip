@@ -106,39 +106,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_mfma_kernel(const
     constexpr int LDS_SLOTS = NS * STAGE > EPI_SLOTS ? NS * STAGE : EPI_SLOTS;
     __shared__ uint4 lds_all[LDS_SLOTS];
 
-    // ---- tile assignment.  Workgroup ids go round-robin to the 8 XCDs (own L2 each): XCD x runs ids x, x + 8, ...
-    // in order.  Row tiles are grouped in bands of BAND that sweep the column (weight) tiles.  While there are 8 whole
-    // bands left, each XCD takes one of them and all eight sweep the columns in step, so that a weight strip is
-    // asked for by all XCDs at about the same time and has to stay in the memory-side cache only that long; every
-    // other sweep runs backwards, starting on the weight strips used last.  The rows left over (fewer than 8 bands)
-    // are split evenly: each XCD gets a contiguous run of their tiles in band order.
-    int tm, tn;
-    {
-        const int x = blockIdx.x % 8, q = blockIdx.x / 8;
-        const int band_tiles = BAND * tiles_n;
-        const int S = tiles_m / (8 * BAND);                  // sweeps with one whole band per XCD
-        const int P1 = S * band_tiles;
-        int row0, band_rows, in_band;
-        if (q < P1) {
-            const int sidx = q / band_tiles;
-            in_band = q - sidx * band_tiles;
-            row0 = (sidx * 8 + x) * BAND;
-            band_rows = BAND;
-            tn = in_band / band_rows;
-            if (sidx & 1) tn = tiles_n - 1 - tn;
-        } else {
-            const int R = tiles_m - S * 8 * BAND;
-            const int nblk = R * tiles_n;
-            const int per = nblk / 8, rem = nblk % 8;       // XCD x gets `per` (+1 if x < rem) blocks
-            const int pid = x * per + (x < rem ? x : rem) + (q - P1);
-            const int band = pid / band_tiles;
-            band_rows = (R - band * BAND) < BAND ? (R - band * BAND) : BAND;
-            in_band = pid - band * band_tiles;
-            row0 = S * 8 * BAND + band * BAND;
-            tn = in_band / band_rows;
-        }
-        tm = row0 + in_band % band_rows;
-    }
+    // ---- tile assignment (gemm_tile_of: XCD-aware bands of row tiles sweeping the column tiles)
+    const GemmTile tile = gemm_tile_of((int)blockIdx.x, tiles_m, tiles_n, BAND);
+    const int tm = tile.tm, tn = tile.tn;
     const int m0 = tm * BM, n0 = tn * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -694,16 +664,7 @@ int launch_cfg(const void* A, const void* W, int M, int Nout, int K, int w_k, in
     if (Nout % BN != 0 || K % (2 * BK) != 0) return RADIX_ERR_UNSUPPORTED;
     const int tiles_m = ceil_div(M, BM), tiles_n = Nout / BN;
     dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WAVES_M * WAVES_N);
-    // Row tiles per band (see the kernel's tile assignment).  The 32 workgroups an XCD runs at a time cover
-    // band x (32 / band) tiles, i.e. band + 32 / band operand strips stream through its L2: 12 for a band of 4
-    // or 8, 18 for 2.  The activation strips of a band are read again for every group of column tiles, and what
-    // serves those re-reads is the 256 MB memory-side cache shared by all XCDs: the eight bands in flight must
-    // leave room in it for the weights, so long rows (large K) take a narrower band.  Measured on MI355X, us per
-    // launch with bands of 8 / 4 / 2 / 1: M 45120, N 4096, K 12288: 4210 / 4168 / 4134 / 4109; N 24576, K 4096:
-    // 7109 / 7025 / 7105 / 7821; N 6144, K 4096: 1827 / 1841 / 1840 / 1929.
-    int band_cfg = 8;
-    while (band_cfg > 1 && 8.0 * band_cfg * BM * (double)K * sizeof(T) > 64.0 * 1024 * 1024) band_cfg /= 2;
-    if (band_cfg == 1 && tiles_n > 16) band_cfg = 2;          // one row of many column tiles: 33 strips per group
+    const int band_cfg = gemm_band_rows(BM, K, (int)sizeof(T), tiles_n);
 #define RADIX_LAUNCH(E)                                                                                       \
     do {                                                                                                      \
         auto kfn = gemm_mfma_kernel<DT, BM, BN, WAVES_M, WAVES_N, E>;                                         \
@@ -805,4 +766,18 @@ int launch_gemm_mfma(const void* A, const void* W, int M, int Nout, int K, int e
     if (op_dtype == RADIX_BF16) return launch_dt<RADIX_BF16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, amap, nf, stream);
     if (op_dtype == RADIX_F16) return launch_dt<RADIX_F16>(A, W, M, Nout, K, w_k, epilogue, out, variant, qe, amap, nf, stream);
     return RADIX_ERR_UNSUPPORTED;
+}
+
+// Host-side views of the tile numbering, for tests (declared in radixmlp_bench.h).
+extern "C" int radix_debug_gemm_tile(int32_t bid, int32_t tiles_m, int32_t tiles_n, int32_t band, int32_t* tm, int32_t* tn) {
+    if (!tm || !tn) return RADIX_ERR_NULL_POINTER;
+    if (tiles_m <= 0 || tiles_n <= 0 || band <= 0 || bid < 0 || (long long)bid >= (long long)tiles_m * tiles_n) return RADIX_ERR_BAD_SIZE;
+    const GemmTile t = gemm_tile_of(bid, tiles_m, tiles_n, band);
+    *tm = t.tm;
+    *tn = t.tn;
+    return RADIX_OK;
+}
+extern "C" int radix_debug_gemm_band(int32_t tile_rows, int32_t K, int32_t tiles_n) {
+    if (tile_rows <= 0 || K <= 0 || tiles_n <= 0) return RADIX_ERR_BAD_SIZE;
+    return gemm_band_rows(tile_rows, K, 2, tiles_n);
 }

@@ -97,6 +97,58 @@ struct ARowMap {
 };
 void launch_gemm_f32(const float* A, const float* W, int M, int Nout, int K, int epilogue, float* out_or_resid,
                      hipStream_t stream);
+// Tile numbering of the MFMA GEMM: which output tile (row tile tm, column tile tn) the workgroup with id `bid`
+// computes, for a launch of tiles_m * tiles_n workgroups.  Workgroup ids go round-robin to the 8 XCDs (own L2
+// each): XCD x runs ids x, x + 8, ... in order.  Row tiles are grouped in bands of `band` that sweep the column
+// (weight) tiles.  While there are 8 whole bands left, each XCD takes one of them and all eight sweep the columns
+// in step, so that a weight strip is asked for by all XCDs at about the same time and has to stay in the
+// memory-side cache only that long; every other sweep runs backwards, starting on the weight strips used last.
+// The rows left over (fewer than 8 bands) are split evenly: each XCD gets a contiguous run of their tiles in band
+// order.  Every tile is computed by exactly one workgroup (tested on the host).
+struct GemmTile { int tm, tn; };
+__host__ __device__ inline GemmTile gemm_tile_of(int bid, int tiles_m, int tiles_n, int band) {
+    const int x = bid % 8, q = bid / 8;
+    const int band_tiles = band * tiles_n;
+    const int S = tiles_m / (8 * band);                  // sweeps with one whole band per XCD
+    const int P1 = S * band_tiles;
+    int row0, band_rows, in_band, tn;
+    if (q < P1) {
+        const int sidx = q / band_tiles;
+        in_band = q - sidx * band_tiles;
+        row0 = (sidx * 8 + x) * band;
+        band_rows = band;
+        tn = in_band / band_rows;
+        if (sidx & 1) tn = tiles_n - 1 - tn;
+    } else {
+        const int R = tiles_m - S * 8 * band;
+        const int nblk = R * tiles_n;
+        const int per = nblk / 8, rem = nblk % 8;       // XCD x gets `per` (+1 if x < rem) blocks
+        const int pid = x * per + (x < rem ? x : rem) + (q - P1);
+        const int b = pid / band_tiles;
+        band_rows = (R - b * band) < band ? (R - b * band) : band;
+        in_band = pid - b * band_tiles;
+        row0 = S * 8 * band + b * band;
+        tn = in_band / band_rows;
+    }
+    GemmTile t;
+    t.tm = row0 + in_band % band_rows;
+    t.tn = tn;
+    return t;
+}
+// Row tiles per band.  The 32 workgroups an XCD runs at a time cover band x (32 / band) tiles, i.e.
+// band + 32 / band operand strips stream through its L2: 12 for a band of 4 or 8, 18 for 2.  The activation strips
+// of a band are read again for every group of column tiles, and what serves those re-reads is the 256 MB
+// memory-side cache shared by all XCDs: the eight bands in flight must leave room in it for the weights, so long
+// rows (large K) take a narrower band.  Measured on MI355X, us per launch with bands of 8 / 4 / 2 / 1:
+// M 45120, N 4096, K 12288: 4210 / 4168 / 4134 / 4109; N 24576, K 4096: 7109 / 7025 / 7105 / 7821;
+// N 6144, K 4096: 1827 / 1841 / 1840 / 1929.
+inline int gemm_band_rows(int bm, int K, int elem_bytes, int tiles_n) {
+    int band = 8;
+    while (band > 1 && 8.0 * band * bm * (double)K * elem_bytes > 64.0 * 1024 * 1024) band /= 2;
+    if (band == 1 && tiles_n > 16) band = 2;          // one row of many column tiles: 33 strips per group
+    return band;
+}
+
 // 16-bit operands (op_dtype RADIX_BF16 or RADIX_F16), fp32 accumulate.  variant 0 = pick a tile shape.
 // w_k: row length of W.  w_k == K is the plain product; w_k == K / 2 multiplies A = [hi | lo] against
 // the weights repeated twice along k, i.e. C = (hi + lo) * W^T.
